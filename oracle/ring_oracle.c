@@ -1,0 +1,353 @@
+/*
+ * ring_oracle.c -- CPU oracle for ring Reduce-Scatter / All-Gather / All-Reduce
+ * over W simulated ranks.  TEST INFRASTRUCTURE ONLY: nothing in the product
+ * library links, includes or calls this file; it shares no code with the HIP
+ * path.  It is deliberately plain and slow so that it can be checked against
+ * the definitions by eye.
+ *
+ * What is replayed.  The paper names All-Reduce, All-Gather and Reduce-Scatter
+ * as the collectives of data-parallel training (Section 1; Appendix B.1,
+ * "Communication patterns in DL"; Appendix D.4 and Table "Communication
+ * patterns across DeepSpeed ZeRO stages") and says that reductions run on the
+ * GPU (Appendix E.3), but leaves the inside of the collectives to the vendor
+ * libraries (Section 4.1 "Key Approach", Section 4.2).  The algorithm below is
+ * therefore the textbook ring: W-1 Reduce-Scatter steps followed by W-1
+ * All-Gather steps, written as literal message passing -- in every step each
+ * rank first puts one block into its successor's inbox, then every rank
+ * consumes its own inbox.  Because all sends of a step complete before any
+ * receive of that step is applied, "all ranks act simultaneously" holds by
+ * construction.
+ *
+ * Conventions (the paper is silent on them; they are the readings this
+ * project fixes):
+ *   - ring[] is a permutation of 0..W-1; next(r) is the entry after r in
+ *     ring[], cyclically; pos(r) is r's index in ring[].
+ *   - All-Reduce splits the count-element vector into W blocks of
+ *     B = ceil(count / W) elements; block c covers
+ *     [min(c*B, count), min((c+1)*B, count)).  Trailing blocks may be short or
+ *     empty.  Reduce-Scatter / All-Gather take B = recvcount / sendcount.
+ *   - Reduce-Scatter step s (0 <= s <= W-2): rank r sends block
+ *     ring[(pos(r) - s - 1) mod W] and receives block ring[(pos(r) - s - 2) mod W].
+ *     After the last step rank r holds the finished block r.
+ *   - All-Gather step s: rank r sends block ring[(pos(r) - s) mod W] and
+ *     receives block ring[(pos(r) - s - 1) mod W].
+ *   - One hop of the reduction, per element:
+ *         partial = round_T( f32(incoming) + f32(local) )
+ *     incoming operand on the left, one IEEE binary32 addition (round to
+ *     nearest even), then one conversion to the wire type T with round to
+ *     nearest even.  Subnormals are kept, overflow gives infinity, NaN
+ *     propagates.  int32 adds modulo 2^32.
+ *   - A chunk is a contiguous run of chunk_elems elements inside a block.  It
+ *     only orders the element loop; it never changes a value.
+ *
+ * Pins (tests/, marker "not gpu"): exact-rational brute force of the closed
+ * form fold on tiny inputs; the hand-derived cancellation example under
+ * tests/golden/; W = 2 against numpy / torch elementwise adds; integer-valued
+ * inputs against exact integer sums; conversions against numpy float16 and
+ * torch bfloat16 over all 2^16 patterns and sampled fp32 patterns; set-based
+ * simulation of the block tables for every W <= 16.  The paper prints no value
+ * for this path, so parity against the paper itself is unpinned; every pin is
+ * derived from the arithmetic.
+ *
+ * Build: gcc -O2 -std=c11 -fopenmp -ffp-contract=off -fPIC -shared
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_FP32 = 0, ORC_BF16 = 1, ORC_FP16 = 2, ORC_INT32 = 3 };
+enum { ORC_OK = 0, ORC_BAD_ARG = 1, ORC_NO_MEM = 2 };
+enum { ORC_PHASE_RS = 0, ORC_PHASE_AG = 1 };
+
+/* ------------------------------------------------------------------ */
+/* bit views                                                           */
+/* ------------------------------------------------------------------ */
+static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/* ------------------------------------------------------------------ */
+/* bfloat16: 1 sign, 8 exponent, 7 fraction bits = top half of binary32 */
+/* ------------------------------------------------------------------ */
+float orc_bf16_to_f32(uint16_t h) { return bits_f32((uint32_t)h << 16); }
+
+uint16_t orc_f32_to_bf16(float f)
+{
+    uint32_t u = f32_bits(f);
+    uint32_t keep = u >> 16;         /* the 16 bits that survive          */
+    uint32_t drop = u & 0xFFFFu;     /* the 16 bits that are rounded away */
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u)        /* NaN stays NaN (quiet)   */
+        return (uint16_t)(keep | 0x0040u);
+    if (drop > 0x8000u) keep += 1;              /* above half: up          */
+    else if (drop == 0x8000u && (keep & 1u)) keep += 1; /* tie: to even    */
+    /* a carry out of the fraction moves into the exponent, and the largest
+       finite value carries into the infinity pattern: both are what IEEE
+       round-to-nearest-even prescribes */
+    return (uint16_t)keep;
+}
+
+/* ------------------------------------------------------------------ */
+/* binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits            */
+/* ------------------------------------------------------------------ */
+float orc_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1Fu;
+    uint32_t m = h & 0x3FFu;
+    if (e == 0x1Fu)                               /* inf / NaN */
+        return bits_f32(sign | 0x7F800000u | (m << 13));
+    if (e == 0) {                                 /* zero / subnormal: m * 2^-24 */
+        float mag = ldexpf((float)m, -24);
+        return sign ? -mag : mag;
+    }
+    return bits_f32(sign | ((e + 112u) << 23) | (m << 13));
+}
+
+uint16_t orc_f32_to_f16(float f)
+{
+    uint32_t u = f32_bits(f);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t e = (u >> 23) & 0xFFu;
+    uint32_t m = u & 0x7FFFFFu;
+    if (e == 0xFFu)
+        return (uint16_t)(sign | (m ? 0x7E00u : 0x7C00u));
+    if (e == 0)            /* |f| < 2^-126, far below half of 2^-24 */
+        return sign;
+    int E = (int)e - 127;                 /* f = sig * 2^(E-23)            */
+    uint32_t sig = 0x800000u | m;         /* 24-bit significand            */
+    if (E > 15)
+        return (uint16_t)(sign | 0x7C00u);
+    uint32_t q, rem, half;
+    uint16_t mag;
+    if (E >= -14) {                       /* normal range of binary16      */
+        q = sig >> 13;                    /* 11 bits, leading one included */
+        rem = sig & 0x1FFFu;
+        half = 0x1000u;
+        mag = (uint16_t)((((uint32_t)(E + 15)) << 10) | (q & 0x3FFu));
+    } else {                              /* subnormal: multiples of 2^-24 */
+        int s = -(E + 1);                 /* q = sig / 2^s                 */
+        if (s > 24)                       /* below half an ulp             */
+            return sign;
+        q = sig >> s;
+        rem = sig & ((1u << s) - 1u);
+        half = 1u << (s - 1);
+        mag = (uint16_t)q;
+    }
+    if (rem > half || (rem == half && (mag & 1u)))
+        mag = (uint16_t)(mag + 1);        /* carry may reach exponent / inf */
+    return (uint16_t)(sign | mag);
+}
+
+/* ------------------------------------------------------------------ */
+/* one hop: partial = round_T(f32(incoming) + f32(local))              */
+/* ------------------------------------------------------------------ */
+float    orc_hop_f32 (float incoming, float local)       { return incoming + local; }
+uint16_t orc_hop_bf16(uint16_t incoming, uint16_t local)
+{ return orc_f32_to_bf16(orc_bf16_to_f32(incoming) + orc_bf16_to_f32(local)); }
+uint16_t orc_hop_f16 (uint16_t incoming, uint16_t local)
+{ return orc_f32_to_f16(orc_f16_to_f32(incoming) + orc_f16_to_f32(local)); }
+int32_t  orc_hop_i32 (int32_t incoming, int32_t local)
+{ return (int32_t)((uint32_t)incoming + (uint32_t)local); }
+
+/* element-wise hop over a run: local[i] = hop(inbox[i], local[i]) */
+static void hop_run(void *local, const void *inbox, size_t n, int dtype)
+{
+    ptrdiff_t i, nn = (ptrdiff_t)n;
+    switch (dtype) {
+    case ORC_FP32: {
+        float *l = (float *)local; const float *in = (const float *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = orc_hop_f32(in[i], l[i]);
+    } break;
+    case ORC_BF16: {
+        uint16_t *l = (uint16_t *)local; const uint16_t *in = (const uint16_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = orc_hop_bf16(in[i], l[i]);
+    } break;
+    case ORC_FP16: {
+        uint16_t *l = (uint16_t *)local; const uint16_t *in = (const uint16_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = orc_hop_f16(in[i], l[i]);
+    } break;
+    default: {
+        int32_t *l = (int32_t *)local; const int32_t *in = (const int32_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = orc_hop_i32(in[i], l[i]);
+    } break;
+    }
+}
+
+/* plain copy of a run (the All-Gather hop) */
+static void copy_run(void *dst, const void *src, size_t nbytes)
+{
+    ptrdiff_t i, nn = (ptrdiff_t)nbytes;
+    unsigned char *d = (unsigned char *)dst; const unsigned char *s = (const unsigned char *)src;
+    #pragma omp parallel for schedule(static) if (nn > 262144)
+    for (i = 0; i < nn; ++i) d[i] = s[i];
+}
+
+/* ------------------------------------------------------------------ */
+/* ring tables                                                         */
+/* ------------------------------------------------------------------ */
+static int wrap(int a, int W) { a %= W; return a < 0 ? a + W : a; }
+
+size_t orc_esize(int dtype) { return (dtype == ORC_BF16 || dtype == ORC_FP16) ? 2u : 4u; }
+
+static int ring_ok(int W, const int *ring, int *pos)
+{
+    int k;
+    for (k = 0; k < W; ++k) pos[k] = -1;
+    for (k = 0; k < W; ++k) {
+        int r = ring ? ring[k] : k;
+        if (r < 0 || r >= W || pos[r] != -1) return 0;
+        pos[r] = k;
+    }
+    return 1;
+}
+static int ring_at(const int *ring, int k) { return ring ? ring[k] : k; }
+
+/* which block rank `rank` sends and which it receives at (phase, step) */
+int orc_ring_step(int W, const int *ring, int phase, int step, int rank,
+                  int *send_block, int *recv_block)
+{
+    int pos[64];
+    if (W < 1 || W > 64 || rank < 0 || rank >= W || step < 0 || step > W - 2) return ORC_BAD_ARG;
+    if (phase != ORC_PHASE_RS && phase != ORC_PHASE_AG) return ORC_BAD_ARG;
+    if (!ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    int p = pos[rank];
+    if (phase == ORC_PHASE_RS) {
+        *send_block = ring_at(ring, wrap(p - step - 1, W));
+        *recv_block = ring_at(ring, wrap(p - step - 2, W));
+    } else {
+        *send_block = ring_at(ring, wrap(p - step, W));
+        *recv_block = ring_at(ring, wrap(p - step - 1, W));
+    }
+    return ORC_OK;
+}
+
+/* block c of a vector cut into pieces of B elements */
+static void block_range(size_t count, size_t B, int c, size_t *lo, size_t *hi)
+{
+    size_t a = (size_t)c * B, b = a + B;
+    if (a > count) a = count;
+    if (b > count) b = count;
+    *lo = a; *hi = b;
+}
+
+/* ------------------------------------------------------------------ */
+/* the ring, as message passing over work[r] (count elements each)     */
+/* ------------------------------------------------------------------ */
+static int ring_phase(void *const *work, int W, size_t count, size_t B, int dtype,
+                      const int *ring, size_t chunk_elems, int phase)
+{
+    int pos[64], r, s;
+    size_t es = orc_esize(dtype);
+    if (!ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    if (W == 1 || count == 0 || B == 0) return ORC_OK;
+
+    /* one inbox per rank, one block wide */
+    unsigned char **inbox = (unsigned char **)calloc((size_t)W, sizeof *inbox);
+    if (!inbox) return ORC_NO_MEM;
+    for (r = 0; r < W; ++r) {
+        inbox[r] = (unsigned char *)malloc(B * es);
+        if (!inbox[r]) { for (s = 0; s < r; ++s) free(inbox[s]); free(inbox); return ORC_NO_MEM; }
+    }
+
+    for (s = 0; s <= W - 2; ++s) {
+        /* every rank sends one block to its successor ... */
+        for (r = 0; r < W; ++r) {
+            int sb, rb; size_t lo, hi;
+            orc_ring_step(W, ring, phase, s, r, &sb, &rb);
+            int nxt = ring_at(ring, wrap(pos[r] + 1, W));
+            block_range(count, B, sb, &lo, &hi);
+            copy_run(inbox[nxt], (const unsigned char *)work[r] + lo * es, (hi - lo) * es);
+        }
+        /* ... then every rank consumes what arrived, chunk by chunk */
+        for (r = 0; r < W; ++r) {
+            int sb, rb; size_t lo, hi, c0;
+            orc_ring_step(W, ring, phase, s, r, &sb, &rb);
+            block_range(count, B, rb, &lo, &hi);
+            size_t len = hi - lo, C = chunk_elems ? chunk_elems : len;
+            for (c0 = 0; c0 < len; c0 += C) {
+                size_t n = (len - c0 < C) ? len - c0 : C;
+                unsigned char *mine = (unsigned char *)work[r] + (lo + c0) * es;
+                const unsigned char *got = inbox[r] + c0 * es;
+                if (phase == ORC_PHASE_RS) hop_run(mine, got, n, dtype);
+                else                       copy_run(mine, got, n * es);
+            }
+        }
+    }
+    for (r = 0; r < W; ++r) free(inbox[r]);
+    free(inbox);
+    return ORC_OK;
+}
+
+static int args_ok(int W, int dtype) { return W >= 1 && W <= 64 && dtype >= 0 && dtype <= 3; }
+
+/* All-Reduce (sum), in place on work[r]: on entry rank r's input, on exit the
+   ring-order sum in every work[r]. */
+int orc_allreduce(void *const *work, int W, size_t count, int dtype,
+                  const int *ring, size_t chunk_elems)
+{
+    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
+    size_t B = (count + (size_t)W - 1) / (size_t)W;
+    int rc = ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_RS);
+    if (rc) return rc;
+    return ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_AG);
+}
+
+/* Reduce-Scatter (sum): work[r] holds W*recvcount elements (rank r's full
+   input; used as scratch, contents undefined on exit); out[r] receives
+   recvcount elements = block r of the ring-order sum. */
+int orc_reduce_scatter(void *const *work, void *const *out, int W, size_t recvcount,
+                       int dtype, const int *ring, size_t chunk_elems)
+{
+    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
+    int rc = ring_phase(work, W, (size_t)W * recvcount, recvcount, dtype, ring,
+                        chunk_elems, ORC_PHASE_RS);
+    if (rc) return rc;
+    size_t es = orc_esize(dtype);
+    for (int r = 0; r < W; ++r)
+        memcpy(out[r], (const unsigned char *)work[r] + (size_t)r * recvcount * es, recvcount * es);
+    return ORC_OK;
+}
+
+/* All-Gather: in[r] holds sendcount elements; out[r] (W*sendcount elements)
+   ends with block q equal to in[q] for every q. */
+int orc_all_gather(const void *const *in, void *const *out, int W, size_t sendcount,
+                   int dtype, const int *ring, size_t chunk_elems)
+{
+    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype);
+    for (int r = 0; r < W; ++r)   /* each rank starts with its own block in place */
+        memcpy((unsigned char *)out[r] + (size_t)r * sendcount * es, in[r], sendcount * es);
+    return ring_phase(out, W, (size_t)W * sendcount, sendcount, dtype, ring,
+                      chunk_elems, ORC_PHASE_AG);
+}
+
+/* bulk conversions, for the conversion pins */
+void orc_f32_to_bf16_n(const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_bf16(x[i]); }
+void orc_f32_to_f16_n (const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_f16(x[i]); }
+void orc_bf16_to_f32_n(const uint16_t *x, float *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_bf16_to_f32(x[i]); }
+void orc_f16_to_f32_n (const uint16_t *x, float *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f16_to_f32(x[i]); }
+/* y[i] = hop(a[i], b[i]) for the hop pins */
+void orc_hop_n(const void *a, const void *b, void *y, size_t n, int dtype)
+{
+    memcpy(y, b, n * orc_esize(dtype));
+    hop_run(y, a, n, dtype);
+}
+
+/* thread control for the timing harness: 0 = leave the OpenMP default */
+int orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n; return 1;
+#endif
+}

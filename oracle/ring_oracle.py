@@ -1,0 +1,165 @@
+"""ctypes front end of the CPU oracle (ring_oracle.c) on numpy arrays.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+CPU-baseline leg of the benchmark; never by the product package.  It shares no
+code with the HIP path and does not import it.
+
+Wire types are passed as numpy arrays: float32 for fp32, int32 for int32 and
+uint16 bit patterns for bf16 / fp16 (numpy has no bfloat16, and bit patterns
+keep comparisons exact).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+FP32, BF16, FP16, INT32 = 0, 1, 2, 3
+PHASE_RS, PHASE_AG = 0, 1
+NP_WIRE = {FP32: np.float32, BF16: np.uint16, FP16: np.uint16, INT32: np.int32}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ring_oracle.c")
+_LIB = os.path.join(_HERE, "libring_oracle.so")
+GCC_FLAGS = ["-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared"]
+
+
+def build(force=False):
+    """Compile ring_oracle.c with gcc (no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *GCC_FLAGS, _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        vpp = ctypes.POINTER(ctypes.c_void_p)
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.orc_ring_step.argtypes = [ctypes.c_int, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ip]
+        L.orc_allreduce.argtypes = [vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_size_t]
+        L.orc_reduce_scatter.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_size_t]
+        L.orc_all_gather.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_size_t]
+        for name in ("orc_f32_to_bf16_n", "orc_f32_to_f16_n", "orc_bf16_to_f32_n", "orc_f16_to_f32_n"):
+            getattr(L, name).argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t]
+            getattr(L, name).restype = None
+        L.orc_hop_n.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        L.orc_hop_n.restype = None
+        L.orc_set_threads.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def _ring_arg(ring, W):
+    if ring is None:
+        return None
+    ring = [int(x) for x in ring]
+    assert len(ring) == W
+    return (ctypes.c_int * W)(*ring)
+
+
+def _ptrs(arrays):
+    return (ctypes.c_void_p * len(arrays))(*[a.ctypes.data for a in arrays])
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def _wire(a, dtype):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == NP_WIRE[dtype] and a.ndim == 1, (a.dtype, dtype)
+    return a
+
+
+def set_threads(n):
+    """Set the OpenMP thread count (0 keeps the default); returns the count in use."""
+    return lib().orc_set_threads(int(n))
+
+
+def ring_step(W, ring, phase, step, rank):
+    """(send_block, recv_block) of `rank` at (phase, step)."""
+    sb, rb = ctypes.c_int(-1), ctypes.c_int(-1)
+    _check(lib().orc_ring_step(W, _ring_arg(ring, W), phase, step, rank, ctypes.byref(sb), ctypes.byref(rb)),
+           "ring_step")
+    return sb.value, rb.value
+
+
+def allreduce(inputs, dtype, ring=None, chunk_elems=0):
+    """Ring All-Reduce (sum).  inputs: W arrays of `count` wire elements.
+    Returns W new arrays; the inputs are left untouched."""
+    W = len(inputs)
+    work = [_wire(a, dtype).copy() for a in inputs]
+    count = work[0].size
+    assert all(w.size == count for w in work)
+    _check(lib().orc_allreduce(_ptrs(work), W, count, dtype, _ring_arg(ring, W), chunk_elems), "allreduce")
+    return work
+
+
+def reduce_scatter(inputs, dtype, ring=None, chunk_elems=0):
+    """Ring Reduce-Scatter (sum).  inputs: W arrays of W*recvcount elements.
+    Returns W arrays of recvcount elements (rank r gets block r)."""
+    W = len(inputs)
+    work = [_wire(a, dtype).copy() for a in inputs]
+    total = work[0].size
+    assert total % W == 0 and all(w.size == total for w in work)
+    n = total // W
+    out = [np.empty(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_reduce_scatter(_ptrs(work), _ptrs(out), W, n, dtype, _ring_arg(ring, W), chunk_elems),
+           "reduce_scatter")
+    return out
+
+
+def all_gather(inputs, dtype, ring=None, chunk_elems=0):
+    """Ring All-Gather.  inputs: W arrays of sendcount elements.
+    Returns W arrays of W*sendcount elements."""
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    n = src[0].size
+    assert all(s.size == n for s in src)
+    out = [np.zeros(W * n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_all_gather(_ptrs(src), _ptrs(out), W, n, dtype, _ring_arg(ring, W), chunk_elems),
+           "all_gather")
+    return out
+
+
+def hop(incoming, local, dtype):
+    """Element-wise single hop: round_T(f32(incoming) + f32(local))."""
+    a, b = _wire(incoming, dtype), _wire(local, dtype)
+    assert a.size == b.size
+    y = np.empty_like(a)
+    lib().orc_hop_n(a.ctypes.data, b.ctypes.data, y.ctypes.data, a.size, dtype)
+    return y
+
+
+def f32_to_bf16(x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty(x.shape, np.uint16)
+    lib().orc_f32_to_bf16_n(x.ctypes.data, y.ctypes.data, x.size)
+    return y
+
+
+def f32_to_f16(x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty(x.shape, np.uint16)
+    lib().orc_f32_to_f16_n(x.ctypes.data, y.ctypes.data, x.size)
+    return y
+
+
+def bf16_to_f32(x):
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    y = np.empty(x.shape, np.float32)
+    lib().orc_bf16_to_f32_n(x.ctypes.data, y.ctypes.data, x.size)
+    return y
+
+
+def f16_to_f32(x):
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    y = np.empty(x.shape, np.float32)
+    lib().orc_f16_to_f32_n(x.ctypes.data, y.ctypes.data, x.size)
+    return y
