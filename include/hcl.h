@@ -1,0 +1,211 @@
+/*
+ * hcl.h -- C ABI of libhcl: ring Reduce-Scatter / All-Gather / All-Reduce over
+ * W simulated ranks whose buffers all live in one GPU's memory (or, for the
+ * staged transport, partly in pinned host memory).
+ *
+ * The paper's library presents the vendor collective libraries' call shape to
+ * the framework -- send buffer, receive buffer, count, datatype, reduction
+ * operator, stream (Section 4.4 "Zero Code Modification") -- and leaves the
+ * partitioning of a message and the device kernels to the vendor library
+ * (Section 4.1 "Key Approach", Section 4.2).  This library is that inside for
+ * one GPU: the communicator is replaced by explicit arrays of W per-rank
+ * pointers, and "sending to the next rank" is a read of that rank's buffer.
+ *
+ * Common conventions
+ *   - send[] / recv[] / ring are HOST arrays of length W, read during the call
+ *     and not retained.  The pointers they hold are DEVICE pointers (memory
+ *     the GPU can access at full speed); opts->host_stage is PINNED HOST
+ *     memory mapped into the GPU's address space (hipHostMalloc).
+ *   - Every buffer is owned by the caller.  The library allocates and frees no
+ *     device or pinned memory; scratch comes in through hcl_opts_t.
+ *   - Ring: ring[] is a permutation of 0..W-1 (NULL = identity); rank ring[k]
+ *     sends to rank ring[(k+1) mod W].
+ *   - Result bits.  int32 sums wrap modulo 2^32.  For the float types every
+ *     hop computes round_T(f32(incoming) + f32(local)) with round to nearest
+ *     even, subnormals kept, overflow to infinity, NaN propagated (any NaN
+ *     pattern).  Block c's sum starts with the rank after c in the ring and
+ *     ends at rank c.  Every schedule, transport, chunk size and launch shape
+ *     produces the same bits.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without synchronising; the
+ *     calls only launch kernels, so they may be captured into a HIP graph.
+ *   - Errors: validation is synchronous and happens before anything is
+ *     enqueued; on any status other than HCL_OK nothing was launched (except
+ *     HCL_ERR_HIP, where a launch itself failed part-way).  hcl_last_error()
+ *     gives a thread-local message.  No exceptions, no abort.
+ *   - W in [1, 16].  count == 0 is HCL_OK and a no-op.  chunk_bytes == 0 means
+ *     one chunk per block; otherwise it must be a positive multiple of the
+ *     element size.  A chunk only orders the work inside a block.
+ *   - Base pointers must be aligned to the element size.  The 128-bit fast
+ *     path needs 16-byte aligned base pointers, block offsets and chunk sizes;
+ *     anything else runs on a slower element-wise path with the same result.
+ *   - Calls are re-entrant; the only global state is cached device properties
+ *     and the thread-local error string.
+ */
+#ifndef HCL_H_
+#define HCL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HCL_MAX_RANKS 16
+#define HCL_VERSION 100
+
+typedef enum {
+  HCL_OK = 0,
+  HCL_ERR_INVALID_ARG = 1, /* null pointer, W out of range, bad ring, misaligned pointer or chunk */
+  HCL_ERR_UNSUPPORTED = 2, /* op other than sum, unknown dtype / schedule / transport combination */
+  HCL_ERR_ALIAS = 3,       /* buffers overlap in a way the schedule cannot honour */
+  HCL_ERR_WORKSPACE = 4,   /* opts->workspace or opts->host_stage missing or too small */
+  HCL_ERR_HIP = 5          /* a HIP runtime call failed */
+} hcl_status_t;
+
+typedef enum { HCL_FP32 = 0, HCL_BF16 = 1, HCL_FP16 = 2, HCL_INT32 = 3 } hcl_dtype_t;
+typedef enum { HCL_SUM = 0 } hcl_op_t;
+
+/* STEPWISE: the ring as each rank executes it, one launch per ring step doing
+ *   every rank's reduce-copy (or copy) of that step.
+ * FUSED: one launch per collective; each thread keeps its elements' whole ring
+ *   pass in registers, reading every rank's value once, in ring order, with
+ *   the same per-hop rounding. */
+typedef enum { HCL_SCHED_STEPWISE = 0, HCL_SCHED_FUSED = 1 } hcl_sched_t;
+
+/* DIRECT: a rank reads the incoming block straight out of its predecessor's
+ *   buffer (peer-to-peer mode, Section 2.1 "Intra-node communication").
+ * HOST_STAGED: every block travelling between ranks is written to the
+ *   receiver's inbox in pinned host memory and read back from there by the
+ *   receiver (host-staged path, Section 2.1 "Inter-node communication and
+ *   RDMA"; Appendix F.1), local operands and results stay in device memory. */
+typedef enum { HCL_XPORT_DIRECT = 0, HCL_XPORT_HOST_STAGED = 1 } hcl_xport_t;
+
+typedef enum { HCL_KIND_ALLREDUCE = 0, HCL_KIND_REDUCE_SCATTER = 1, HCL_KIND_ALL_GATHER = 2 } hcl_kind_t;
+typedef enum { HCL_PHASE_RS = 0, HCL_PHASE_AG = 1 } hcl_phase_t;
+
+/* Optional settings; a NULL hcl_opts_t* or a zero-filled struct means defaults. */
+typedef struct hcl_opts {
+  const int *ring;         /* host array, permutation of 0..W-1; NULL = identity            */
+  int sched;               /* hcl_sched_t                                                   */
+  int xport;               /* hcl_xport_t                                                   */
+  void *workspace;         /* device scratch; see hcl_workspace_bytes                       */
+  size_t workspace_bytes;
+  void *host_stage;        /* pinned host inboxes; see hcl_host_stage_bytes                 */
+  size_t host_stage_bytes;
+  int threads;             /* threads per workgroup: 0 = default, else 64..1024, multiple of 64 */
+  int blocks;              /* workgroups per launch: 0 = default (a multiple of the CU count)   */
+  int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default, 1, 2, 4 or 8 */
+  int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
+  int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
+                              writes the finished block into the next rank's buffer and the
+                              first All-Gather step is dropped (same bits, one read fewer)   */
+  void *const *events;     /* measurement hook: host array of n_events hipEvent_t; event k is
+                              recorded on the stream before launch k, and one more after the
+                              last launch; launches beyond n_events-1 are not bracketed     */
+  int n_events;
+  int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
+} hcl_opts_t;
+
+/* One unit of the ring schedule, as hcl_schedule_items reports it. */
+typedef struct hcl_work_item {
+  int phase;               /* hcl_phase_t                                            */
+  int step;                /* 0 .. W-2                                               */
+  int rank;                /* the rank doing the work                                */
+  int from_rank;           /* its predecessor in the ring, whose block arrives       */
+  int block;               /* block index received (and, in RS, reduced)             */
+  int send_block;          /* block this rank passes on in the same step             */
+  uint64_t chunk;          /* chunk index inside the block                           */
+  uint64_t elem_offset;    /* first element, counted from the start of the block     */
+  uint64_t elem_count;     /* elements in this chunk                                 */
+  uint64_t vec_offset;     /* first element, counted from the start of the full vector */
+} hcl_work_item_t;
+
+/*
+ * All-Reduce (sum).  send[r] and recv[r] hold `count` elements; afterwards
+ * every recv[r] holds the ring-order sum over all ranks (bit-identical across
+ * ranks).  The vector is cut into W blocks of ceil(count / W) elements; the
+ * collective is W-1 Reduce-Scatter steps then W-1 All-Gather steps (Section 1;
+ * Appendix B.1 "Communication patterns in DL"; Appendix D.4).
+ * In place: recv[r] == send[r] for every r (all ranks or none).  Otherwise
+ * no recv buffer may overlap any other buffer, and send[] is left untouched.
+ * Needs no workspace.  HOST_STAGED needs opts->host_stage.
+ */
+hcl_status_t hcl_allreduce_sim(const void *const *send, void *const *recv, int W, size_t count,
+                               hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
+                               const hcl_opts_t *opts, void *stream);
+
+/*
+ * Reduce-Scatter (sum): the gradient half of ZeRO-2/3 (Appendix D.4, Table
+ * "Communication patterns across DeepSpeed ZeRO stages").  send[r] holds
+ * W * recvcount elements, recv[r] receives recvcount elements = block r of the
+ * ring-order sum.
+ * In place: recv[r] == send[r] + r * recvcount (elements) for every r; the
+ * other blocks of send[r] are then used for partial sums and left undefined.
+ * Out of place with the STEPWISE schedule and W > 2, partial sums live in
+ * opts->workspace (hcl_workspace_bytes); send[] is left untouched.
+ */
+hcl_status_t hcl_reduce_scatter_sim(const void *const *send, void *const *recv, int W, size_t recvcount,
+                                    hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
+                                    const hcl_opts_t *opts, void *stream);
+
+/*
+ * All-Gather: the parameter half of ZeRO-3 (same passages).  send[r] holds
+ * sendcount elements, recv[r] receives W * sendcount elements, block q equal
+ * to send[q].  In place: send[r] == recv[r] + r * sendcount for every r.
+ */
+hcl_status_t hcl_all_gather_sim(const void *const *send, void *const *recv, int W, size_t sendcount,
+                                hcl_dtype_t dtype, size_t chunk_bytes,
+                                const hcl_opts_t *opts, void *stream);
+
+/* Device scratch the call of this kind and shape needs in opts->workspace
+ * (0 for everything except an out-of-place STEPWISE Reduce-Scatter with W > 2,
+ * where the caller cannot say "in place" here: the figure is the out-of-place
+ * one).  `count` is the per-call count argument of that entry point.  Returns
+ * 0 on invalid arguments too. */
+size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
+                           const hcl_opts_t *opts);
+
+/* Pinned host memory the HOST_STAGED transport needs in opts->host_stage:
+ * two inbox slots of one block per rank.  0 for the DIRECT transport. */
+size_t hcl_host_stage_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
+                            const hcl_opts_t *opts);
+
+/* Ring chunk scheduler, host only.  Which block `rank` sends and which it
+ * receives at (phase, step): Reduce-Scatter step s sends
+ * ring[(pos - s - 1) mod W] and receives (and reduces) ring[(pos - s - 2) mod W];
+ * All-Gather step s sends ring[(pos - s) mod W] and receives
+ * ring[(pos - s - 1) mod W], pos being the rank's index in ring[]. */
+hcl_status_t hcl_ring_step(int W, const int *ring, int phase, int step, int rank,
+                           int *send_block, int *recv_block);
+
+/* Enumerates the work items of one ring step (every rank, every chunk, in
+ * launch order: chunk-major, then ring position) for a vector of W blocks of
+ * `block_elems` elements where the last block may be shorter: `count` is the
+ * full vector length (All-Reduce: count; RS / AG: W * per-rank count).
+ * Writes at most max_items items and always reports the total in *n_items.
+ * Host only. */
+hcl_status_t hcl_schedule_items(int W, const int *ring, size_t count, hcl_dtype_t dtype,
+                                size_t chunk_bytes, int phase, int step,
+                                hcl_work_item_t *items, size_t max_items, size_t *n_items);
+
+/* Measurement helpers: thin wrappers over hipEventCreate / hipEventDestroy /
+ * hipEventElapsedTime so that a caller without HIP headers can time launches
+ * on the stream they run on (see hcl_opts_t.events). */
+hcl_status_t hcl_events_create(int n, void **events_out);
+hcl_status_t hcl_events_destroy(int n, void *const *events);
+hcl_status_t hcl_event_record(void *event, void *stream);
+hcl_status_t hcl_event_elapsed_ms(void *start, void *stop, float *ms);
+
+/* Number of compute units of the current device (cached), or -1. */
+int hcl_device_cu_count(void);
+
+const char *hcl_status_string(hcl_status_t s);
+const char *hcl_last_error(void);
+int hcl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCL_H_ */

@@ -101,6 +101,16 @@ def allreduce(inputs, dtype, ring=None, chunk_elems=0):
     return work
 
 
+def allreduce_inplace(work, dtype, ring=None, chunk_elems=0):
+    """Ring All-Reduce replayed in place on the W arrays in `work` (no copies:
+    this is the call the timing harness brackets)."""
+    W = len(work)
+    for w in work:
+        assert w.dtype == NP_WIRE[dtype] and w.flags.c_contiguous and w.size == work[0].size
+    _check(lib().orc_allreduce(_ptrs(work), W, work[0].size, dtype, _ring_arg(ring, W), chunk_elems), "allreduce")
+    return work
+
+
 def reduce_scatter(inputs, dtype, ring=None, chunk_elems=0):
     """Ring Reduce-Scatter (sum).  inputs: W arrays of W*recvcount elements.
     Returns W arrays of recvcount elements (rank r gets block r)."""

@@ -1,0 +1,708 @@
+// C ABI of libhcl: validation, the ring chunk scheduler and the per-step
+// launch plans.  Every step of a collective is a kernel launch on the caller's
+// stream; nothing is computed on the host.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "hcl.h"
+#include "reduce_copy.h"
+#include "ring_sched.h"
+
+using namespace hcl;
+
+// ---------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static hcl_status_t fail(hcl_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+extern "C" const char* hcl_status_string(hcl_status_t s) {
+  switch (s) {
+    case HCL_OK: return "HCL_OK";
+    case HCL_ERR_INVALID_ARG: return "HCL_ERR_INVALID_ARG";
+    case HCL_ERR_UNSUPPORTED: return "HCL_ERR_UNSUPPORTED";
+    case HCL_ERR_ALIAS: return "HCL_ERR_ALIAS";
+    case HCL_ERR_WORKSPACE: return "HCL_ERR_WORKSPACE";
+    case HCL_ERR_HIP: return "HCL_ERR_HIP";
+  }
+  return "HCL_ERR_UNKNOWN";
+}
+extern "C" const char* hcl_last_error(void) { return g_err; }
+extern "C" int hcl_version(void) { return HCL_VERSION; }
+
+// ---------------------------------------------------------------------------
+// scheduler (host only)
+// ---------------------------------------------------------------------------
+bool Ring::init(int W_, const int* ring) {
+  if (W_ < 1 || W_ > kMaxRanks) return false;
+  W = W_;
+  for (int r = 0; r < W; ++r) pos[r] = -1;
+  for (int k = 0; k < W; ++k) {
+    const int r = ring ? ring[k] : k;
+    if (r < 0 || r >= W || pos[r] != -1) return false;
+    order[k] = r;
+    pos[r] = k;
+  }
+  return true;
+}
+
+extern "C" hcl_status_t hcl_ring_step(int W, const int* ring, int phase, int step, int rank,
+                                      int* send_block, int* recv_block) {
+  Ring rg;
+  if (!rg.init(W, ring)) return fail(HCL_ERR_INVALID_ARG, "W must be in [1,%d] and ring a permutation of 0..W-1", kMaxRanks);
+  if (rank < 0 || rank >= W) return fail(HCL_ERR_INVALID_ARG, "rank %d out of range", rank);
+  if (step < 0 || step > W - 2) return fail(HCL_ERR_INVALID_ARG, "step %d out of range [0,%d]", step, W - 2);
+  if (!send_block || !recv_block) return fail(HCL_ERR_INVALID_ARG, "null output pointer");
+  if (phase == HCL_PHASE_RS) {
+    *send_block = rg.rs_send(rank, step);
+    *recv_block = rg.rs_recv(rank, step);
+  } else if (phase == HCL_PHASE_AG) {
+    *send_block = rg.ag_send(rank, step);
+    *recv_block = rg.ag_recv(rank, step);
+  } else {
+    return fail(HCL_ERR_INVALID_ARG, "phase must be 0 (reduce-scatter) or 1 (all-gather)");
+  }
+  return HCL_OK;
+}
+
+static bool dtype_ok(int d) { return d >= HCL_FP32 && d <= HCL_INT32; }
+
+extern "C" hcl_status_t hcl_schedule_items(int W, const int* ring, size_t count, hcl_dtype_t dtype,
+                                           size_t chunk_bytes, int phase, int step,
+                                           hcl_work_item_t* items, size_t max_items, size_t* n_items) {
+  Ring rg;
+  if (!rg.init(W, ring)) return fail(HCL_ERR_INVALID_ARG, "W must be in [1,%d] and ring a permutation of 0..W-1", kMaxRanks);
+  if (!dtype_ok(dtype)) return fail(HCL_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+  if (phase != HCL_PHASE_RS && phase != HCL_PHASE_AG) return fail(HCL_ERR_INVALID_ARG, "bad phase");
+  if (!n_items || (max_items && !items)) return fail(HCL_ERR_INVALID_ARG, "null output pointer");
+  const size_t es = elem_size(dtype);
+  if (chunk_bytes % es) return fail(HCL_ERR_INVALID_ARG, "chunk_bytes must be a multiple of the element size");
+  *n_items = 0;
+  if (W == 1 || count == 0) return HCL_OK;
+  if (step < 0 || step > W - 2) return fail(HCL_ERR_INVALID_ARG, "step %d out of range [0,%d]", step, W - 2);
+  BlockMap bm{count, ceil_div(count, (uint64_t)W)};
+  const uint64_t C = chunk_bytes ? chunk_bytes / es : bm.B;
+  const uint64_t nchunks = ceil_div(bm.B, C);
+  size_t n = 0;
+  for (uint64_t j = 0; j < nchunks; ++j) {
+    for (int k = 0; k < W; ++k) {
+      const int r = rg.order[k];
+      const int rb = phase == HCL_PHASE_RS ? rg.rs_recv(r, step) : rg.ag_recv(r, step);
+      const int sb = phase == HCL_PHASE_RS ? rg.rs_send(r, step) : rg.ag_send(r, step);
+      const uint64_t len = bm.len(rb);
+      if (j * C >= len) continue;
+      if (n < max_items) {
+        hcl_work_item_t& it = items[n];
+        it.phase = phase;
+        it.step = step;
+        it.rank = r;
+        it.from_rank = rg.prev(r);
+        it.block = rb;
+        it.send_block = sb;
+        it.chunk = j;
+        it.elem_offset = j * C;
+        it.elem_count = (len - j * C < C) ? len - j * C : C;
+        it.vec_offset = bm.lo(rb) + j * C;
+      }
+      ++n;
+    }
+  }
+  *n_items = n;
+  return HCL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// device info and measurement helpers
+// ---------------------------------------------------------------------------
+extern "C" int hcl_device_cu_count(void) {
+  static thread_local int cached_dev = -1, cached_cus = -1;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return -1; }
+  if (dev != cached_dev) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      return -1;
+    }
+    cached_dev = dev;
+    cached_cus = cus;
+  }
+  return cached_cus;
+}
+
+extern "C" hcl_status_t hcl_events_create(int n, void** out) {
+  if (n < 0 || (n && !out)) return fail(HCL_ERR_INVALID_ARG, "bad event array");
+  for (int i = 0; i < n; ++i) {
+    hipEvent_t e;
+    hipError_t rc = hipEventCreate(&e);
+    if (rc != hipSuccess) {
+      for (int k = 0; k < i; ++k) (void)hipEventDestroy((hipEvent_t)out[k]);
+      return fail(HCL_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(rc));
+    }
+    out[i] = (void*)e;
+  }
+  return HCL_OK;
+}
+extern "C" hcl_status_t hcl_events_destroy(int n, void* const* ev) {
+  if (n < 0 || (n && !ev)) return fail(HCL_ERR_INVALID_ARG, "bad event array");
+  for (int i = 0; i < n; ++i)
+    if (ev[i]) (void)hipEventDestroy((hipEvent_t)ev[i]);
+  return HCL_OK;
+}
+extern "C" hcl_status_t hcl_event_record(void* ev, void* stream) {
+  if (!ev) return fail(HCL_ERR_INVALID_ARG, "null event");
+  hipError_t rc = hipEventRecord((hipEvent_t)ev, (hipStream_t)stream);
+  if (rc != hipSuccess) return fail(HCL_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(rc));
+  return HCL_OK;
+}
+extern "C" hcl_status_t hcl_event_elapsed_ms(void* a, void* b, float* ms) {
+  if (!a || !b || !ms) return fail(HCL_ERR_INVALID_ARG, "null argument");
+  hipError_t rc = hipEventElapsedTime(ms, (hipEvent_t)a, (hipEvent_t)b);
+  if (rc != hipSuccess) return fail(HCL_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(rc));
+  return HCL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// call context
+// ---------------------------------------------------------------------------
+namespace {
+
+struct Range {
+  const char* p;
+  uint64_t bytes;
+  bool overlaps(const Range& o) const {
+    if (!bytes || !o.bytes) return false;
+    return p < o.p + o.bytes && o.p < p + bytes;
+  }
+};
+
+uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
+}
+
+struct Ctx {
+  Ring ring;
+  int W = 0;
+  int dtype = 0;
+  uint64_t es = 4;
+  uint64_t chunk_elems = 0;  // 0 = one chunk per block
+  int sched = 0, xport = 0;
+  bool fuse_rs_ag = false;
+  Tuning tune{};
+  int max_blocks = 0;
+  const hcl_opts_t* opts = nullptr;
+  void* stream = nullptr;
+  int launches = 0;
+
+  hcl_status_t init(int W_, hcl_dtype_t dt, size_t chunk_bytes, const hcl_opts_t* o, void* st) {
+    opts = o;
+    stream = st;
+    if (W_ < 1 || W_ > kMaxRanks) return fail(HCL_ERR_INVALID_ARG, "W = %d outside [1,%d]", W_, kMaxRanks);
+    if (!ring.init(W_, o ? o->ring : nullptr)) return fail(HCL_ERR_INVALID_ARG, "ring is not a permutation of 0..W-1");
+    W = W_;
+    if (!dtype_ok(dt)) return fail(HCL_ERR_UNSUPPORTED, "unknown dtype %d", (int)dt);
+    dtype = dt;
+    es = elem_size(dt);
+    if (chunk_bytes % es) return fail(HCL_ERR_INVALID_ARG, "chunk_bytes %zu is not a multiple of the element size %d", chunk_bytes, (int)es);
+    chunk_elems = chunk_bytes / es;
+    sched = o ? o->sched : 0;
+    xport = o ? o->xport : 0;
+    if (sched != HCL_SCHED_STEPWISE && sched != HCL_SCHED_FUSED) return fail(HCL_ERR_UNSUPPORTED, "unknown schedule %d", sched);
+    if (xport != HCL_XPORT_DIRECT && xport != HCL_XPORT_HOST_STAGED) return fail(HCL_ERR_UNSUPPORTED, "unknown transport %d", xport);
+    if (sched == HCL_SCHED_FUSED && xport == HCL_XPORT_HOST_STAGED)
+      return fail(HCL_ERR_UNSUPPORTED, "the fused schedule has no staged transport: no block travels between ranks");
+    fuse_rs_ag = o && o->fuse_rs_ag;
+    if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
+    if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
+
+    int threads = o && o->threads ? o->threads : env_int("HCL_THREADS", 0);
+    int unroll = o && o->unroll ? o->unroll : env_int("HCL_UNROLL", 0);
+    int blocks = o && o->blocks ? o->blocks : env_int("HCL_BLOCKS", 0);
+    int nt = o && o->nontemporal ? o->nontemporal : env_int("HCL_NONTEMPORAL", 0);
+    if (threads == 0) threads = 256;
+    if (unroll == 0) unroll = 4;
+    if (threads < 64 || threads > 1024 || threads % 64) return fail(HCL_ERR_INVALID_ARG, "threads = %d must be a multiple of 64 in [64,1024]", threads);
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return fail(HCL_ERR_INVALID_ARG, "unroll = %d must be 1, 2, 4 or 8", unroll);
+    if (blocks < 0) return fail(HCL_ERR_INVALID_ARG, "blocks < 0");
+    if (nt < -1 || nt > 1) return fail(HCL_ERR_INVALID_ARG, "nontemporal must be -1, 0 or 1");
+    tune.threads = threads;
+    tune.unroll = unroll;
+    tune.nontemporal = nt >= 0;
+    tune.vec = true;
+    max_blocks = blocks;  // 0 = decide at launch from the CU count
+    return HCL_OK;
+  }
+
+  int grid_for(uint32_t total_tiles) {
+    int cap = max_blocks;
+    if (cap == 0) {
+      int cus = hcl_device_cu_count();
+      if (cus <= 0) cus = 256;
+      cap = cus * (2048 / tune.threads);  // fill every CU's wave slots
+    }
+    return total_tiles < (uint32_t)cap ? (int)total_tiles : cap;
+  }
+
+  hcl_status_t mark(int idx) {
+    if (opts && opts->events && idx < opts->n_events) {
+      hipError_t rc = hipEventRecord((hipEvent_t)opts->events[idx], (hipStream_t)stream);
+      if (rc != hipSuccess) return fail(HCL_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(rc));
+    }
+    return HCL_OK;
+  }
+
+  // Completes the tile grid of a step and launches it.  Empty steps are skipped.
+  hcl_status_t launch(StepArgs& a, int nsrc, int ndst) {
+    if (a.nseg == 0) return HCL_OK;
+    uint64_t maxn = 0;
+    bool al = true;
+    for (uint32_t i = 0; i < a.nseg; ++i) {
+      const Seg& s = a.seg[i];
+      if (s.n > maxn) maxn = s.n;
+      uintptr_t bits = (uintptr_t)s.src0 | (uintptr_t)s.dst0;
+      if (nsrc == 2) bits |= (uintptr_t)s.src1;
+      if (ndst == 2) bits |= (uintptr_t)s.dst1;
+      if (bits & 15) al = false;
+    }
+    uint64_t chunk = (chunk_elems && chunk_elems < maxn) ? chunk_elems : maxn;
+    const uint64_t nchunks = ceil_div(maxn, chunk);
+    if (nchunks > 1 && (chunk * es) % 16) al = false;
+    Tuning t = tune;
+    t.vec = al;
+    const uint64_t tile = tile_elems(dtype, t);
+    const uint64_t tpc = ceil_div(chunk, tile);
+    const uint64_t total = nchunks * a.nseg * tpc;
+    if (total > 0x7FFFFFFFull) return fail(HCL_ERR_INVALID_ARG, "step needs %llu tiles, more than one launch can index", (unsigned long long)total);
+    a.chunk = chunk;
+    a.tiles_per_chunk = (uint32_t)tpc;
+    a.total_tiles = (uint32_t)total;
+    t.blocks = grid_for(a.total_tiles);
+    hcl_status_t st = mark(launches);
+    if (st) return st;
+    int rc = launch_step(a, dtype, nsrc, ndst, t, stream);
+    if (rc) return fail(HCL_ERR_HIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)rc));
+    ++launches;
+    return HCL_OK;
+  }
+
+  hcl_status_t launch(FusedArgs& a) {
+    if (a.count == 0) return HCL_OK;
+    bool al = (a.B * es) % 16 == 0;
+    for (int r = 0; r < W; ++r)
+      if (((uintptr_t)a.src[r] | (uintptr_t)a.dst[r]) & 15) al = false;
+    uint64_t chunk = (chunk_elems && chunk_elems < a.B) ? chunk_elems : a.B;
+    const uint64_t nchunks = ceil_div(a.B, chunk);
+    if (nchunks > 1 && (chunk * es) % 16) al = false;
+    Tuning t = tune;
+    t.vec = al;
+    t.unroll = a.mode == 2 ? 4 : fused_unroll(W);
+    const uint64_t tile = tile_elems(dtype, t);
+    const uint64_t tpc = ceil_div(chunk, tile);
+    const uint64_t total = nchunks * (uint64_t)W * tpc;
+    if (total > 0x7FFFFFFFull) return fail(HCL_ERR_INVALID_ARG, "collective needs %llu tiles, more than one launch can index", (unsigned long long)total);
+    a.chunk = chunk;
+    a.tiles_per_chunk = (uint32_t)tpc;
+    a.total_tiles = (uint32_t)total;
+    t.blocks = grid_for(a.total_tiles);
+    hcl_status_t st = mark(launches);
+    if (st) return st;
+    int rc = launch_fused(a, dtype, t, stream);
+    if (rc) return fail(HCL_ERR_HIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)rc));
+    ++launches;
+    return HCL_OK;
+  }
+
+  hcl_status_t finish() {
+    hcl_status_t st = launches ? mark(launches) : HCL_OK;
+    if (opts && opts->n_launches) *opts->n_launches = launches;
+    return st;
+  }
+};
+
+void add_seg(StepArgs& a, const void* s0, const void* s1, void* d0, void* d1, uint64_t n) {
+  if (n == 0) return;
+  Seg& s = a.seg[a.nseg++];
+  s.src0 = (const char*)s0;
+  s.src1 = (const char*)s1;
+  s.dst0 = (char*)d0;
+  s.dst1 = (char*)d1;
+  s.n = n;
+}
+
+const char* off(const void* p, uint64_t elems, uint64_t es) { return (const char*)p + elems * es; }
+char* off(void* p, uint64_t elems, uint64_t es) { return (char*)p + elems * es; }
+
+hcl_status_t check_ptrs(const void* const* send, void* const* recv, int W, uint64_t es) {
+  if (!send || !recv) return fail(HCL_ERR_INVALID_ARG, "null send / recv array");
+  for (int r = 0; r < W; ++r) {
+    if (!send[r] || !recv[r]) return fail(HCL_ERR_INVALID_ARG, "null buffer for rank %d", r);
+    if (((uintptr_t)send[r] | (uintptr_t)recv[r]) % es) return fail(HCL_ERR_INVALID_ARG, "buffer of rank %d is not aligned to the element size", r);
+  }
+  return HCL_OK;
+}
+
+// recv buffers must not overlap each other, nor any send buffer unless the pair
+// (r, r) is the exact in-place aliasing `inplace_send_of_recv`.
+hcl_status_t check_alias(const void* const* send, void* const* recv, int W, uint64_t send_bytes,
+                         uint64_t recv_bytes, const Range* extra, int n_extra, bool inplace,
+                         bool send_written) {
+  for (int r = 0; r < W; ++r) {
+    Range rr{(const char*)recv[r], recv_bytes};
+    for (int q = 0; q < W; ++q) {
+      if (q != r && rr.overlaps(Range{(const char*)recv[q], recv_bytes}))
+        return fail(HCL_ERR_ALIAS, "recv buffers of ranks %d and %d overlap", r, q);
+      if (!(inplace && q == r) && rr.overlaps(Range{(const char*)send[q], send_bytes}))
+        return fail(HCL_ERR_ALIAS, "recv buffer of rank %d overlaps send buffer of rank %d", r, q);
+      if (send_written && q != r && Range{(const char*)send[r], send_bytes}.overlaps(Range{(const char*)send[q], send_bytes}))
+        return fail(HCL_ERR_ALIAS, "send buffers of ranks %d and %d overlap but are written in place", r, q);
+    }
+    for (int k = 0; k < n_extra; ++k) {
+      if (rr.overlaps(extra[k]) || Range{(const char*)send[r], send_bytes}.overlaps(extra[k]))
+        return fail(HCL_ERR_ALIAS, "workspace / staging memory overlaps a buffer of rank %d", r);
+    }
+  }
+  return HCL_OK;
+}
+
+// Inboxes in pinned host memory: two slots of one block per rank.
+struct Inbox {
+  char* base = nullptr;
+  uint64_t slot_bytes = 0;
+  char* slot(int rank, int parity) const { return base + ((uint64_t)rank * 2 + (parity & 1)) * slot_bytes; }
+};
+
+uint64_t slot_bytes_for(uint64_t block_elems, uint64_t es) { return round_up(block_elems * es, 256); }
+
+hcl_status_t get_inbox(const Ctx& c, uint64_t block_elems, Inbox& ib) {
+  if (c.xport != HCL_XPORT_HOST_STAGED) return HCL_OK;
+  ib.slot_bytes = slot_bytes_for(block_elems, c.es);
+  const uint64_t need = ib.slot_bytes * 2 * c.W;
+  if (!c.opts || !c.opts->host_stage) return fail(HCL_ERR_WORKSPACE, "host-staged transport needs opts->host_stage (%llu bytes)", (unsigned long long)need);
+  if (c.opts->host_stage_bytes < need) return fail(HCL_ERR_WORKSPACE, "host_stage has %zu bytes, %llu needed", c.opts->host_stage_bytes, (unsigned long long)need);
+  if ((uintptr_t)c.opts->host_stage % 16) return fail(HCL_ERR_INVALID_ARG, "host_stage must be 16-byte aligned");
+  ib.base = (char*)c.opts->host_stage;
+  return HCL_OK;
+}
+
+bool size_overflows(uint64_t count, uint64_t mult, uint64_t es) {
+  if (count == 0) return false;
+  const uint64_t lim = (uint64_t)1 << 62;
+  return count > lim / es / (mult ? mult : 1);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// workspace queries
+// ---------------------------------------------------------------------------
+extern "C" size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
+                                      const hcl_opts_t* opts) {
+  (void)chunk_bytes;
+  if (W < 1 || W > kMaxRanks || !dtype_ok(dtype)) return 0;
+  const int sched = opts ? opts->sched : 0, xport = opts ? opts->xport : 0;
+  if (kind != HCL_KIND_REDUCE_SCATTER || sched != HCL_SCHED_STEPWISE || xport != HCL_XPORT_DIRECT || W <= 2) return 0;
+  if (size_overflows(count, 2 * (uint64_t)W, elem_size(dtype))) return 0;
+  return (size_t)(slot_bytes_for(count, elem_size(dtype)) * 2 * W);
+}
+
+extern "C" size_t hcl_host_stage_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
+                                       const hcl_opts_t* opts) {
+  (void)chunk_bytes;
+  if (W < 1 || W > kMaxRanks || !dtype_ok(dtype)) return 0;
+  if (!opts || opts->xport != HCL_XPORT_HOST_STAGED) return 0;
+  uint64_t B = count;
+  if (kind == HCL_KIND_ALLREDUCE) B = ceil_div(count, (uint64_t)W);
+  if (size_overflows(B, 2 * (uint64_t)W, elem_size(dtype))) return 0;
+  return (size_t)(slot_bytes_for(B, elem_size(dtype)) * 2 * W);
+}
+
+// ---------------------------------------------------------------------------
+// the three collectives
+// ---------------------------------------------------------------------------
+
+// Reduce-Scatter steps 0..W-2 over the block map `bm`.
+//   own[r]   : where rank r's own data of a block is read from
+//   part[r]  : full-vector buffer where rank r keeps its partial sums (DIRECT)
+//   first[r] : full-vector buffer the successor reads rank r's block from at step 0
+//   fin[r]   : where rank r's finished block r goes (already offset to the block)
+//   push[r]  : non-null: the finished block r is also stored there (next rank's buffer, offset)
+//   ws       : non-null (with ws_slot bytes per slot): partials live in two
+//              workspace slots per rank instead of part[]
+static hcl_status_t run_rs(Ctx& c, const BlockMap& bm, const void* const* own, char* const* part,
+                           const void* const* first, char* const* fin, char* const* push,
+                           char* ws, uint64_t ws_slot, const Inbox& ib, bool forward_last) {
+  const int W = c.W;
+  const uint64_t es = c.es;
+  const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
+  hcl_status_t st;
+  if (staged) {
+    // every rank puts the block it sends first into its successor's inbox
+    StepArgs a{};
+    for (int k = 0; k < W; ++k) {
+      const int r = c.ring.order[k], sb = c.ring.rs_send(r, 0);
+      add_seg(a, off(first[r], bm.lo(sb), es), nullptr, ib.slot(c.ring.next(r), 0), nullptr, bm.len(sb));
+    }
+    if ((st = c.launch(a, 1, 1))) return st;
+  }
+  for (int s = 0; s <= W - 2; ++s) {
+    const bool last = s == W - 2;
+    StepArgs a{};
+    int ndst = 1;
+    for (int k = 0; k < W; ++k) {
+      const int r = c.ring.order[k], p = c.ring.prev(r), b = c.ring.rs_recv(r, s);
+      const uint64_t lo = bm.lo(b), n = bm.len(b);
+      const char* local = off(own[r], lo, es);
+      if (staged) {
+        const char* in = ib.slot(r, s);
+        char* fwd = ib.slot(c.ring.next(r), s + 1);
+        if (!last) {
+          add_seg(a, in, local, fwd, nullptr, n);  // the partial only travels on
+        } else if (forward_last) {
+          add_seg(a, in, local, fin[r], fwd, n);
+          ndst = 2;
+        } else {
+          add_seg(a, in, local, fin[r], nullptr, n);
+        }
+      } else {
+        const char* in;
+        if (s == 0) in = off(first[p], lo, es);
+        else if (ws) in = ws + ((uint64_t)p * 2 + ((s - 1) & 1)) * ws_slot;
+        else in = off(part[p], lo, es);
+        char* out;
+        if (last) out = fin[r];
+        else if (ws) out = ws + ((uint64_t)r * 2 + (s & 1)) * ws_slot;
+        else out = off(part[r], lo, es);
+        if (last && push) {
+          add_seg(a, in, local, out, push[r], n);
+          ndst = 2;
+        } else {
+          add_seg(a, in, local, out, nullptr, n);
+        }
+      }
+    }
+    if ((st = c.launch(a, 2, ndst))) return st;
+  }
+  return HCL_OK;
+}
+
+// All-Gather steps first_step..W-2 over `bm`; buf[r] is rank r's full vector.
+// src0[r] non-null: at step 0 the successor of r reads r's block from there
+// instead of buf[r] (out-of-place All-Gather).  parity0: inbox slot parity the
+// block of step 0 arrives in.
+static hcl_status_t run_ag(Ctx& c, const BlockMap& bm, char* const* buf, const void* const* src0,
+                           int first_step, const Inbox& ib, int parity0) {
+  const int W = c.W;
+  const uint64_t es = c.es;
+  const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
+  hcl_status_t st;
+  for (int s = first_step; s <= W - 2; ++s) {
+    const bool last = s == W - 2;
+    StepArgs a{};
+    int ndst = 1;
+    for (int k = 0; k < W; ++k) {
+      const int r = c.ring.order[k], p = c.ring.prev(r), g = c.ring.ag_recv(r, s);
+      const uint64_t lo = bm.lo(g), n = bm.len(g);
+      char* out = off(buf[r], lo, es);
+      if (staged) {
+        const char* in = ib.slot(r, parity0 + s);
+        if (!last) {
+          add_seg(a, in, nullptr, out, ib.slot(c.ring.next(r), parity0 + s + 1), n);
+          ndst = 2;
+        } else {
+          add_seg(a, in, nullptr, out, nullptr, n);
+        }
+      } else {
+        const char* in = (s == 0 && src0) ? (const char*)src0[p] : off(buf[p], lo, es);
+        add_seg(a, in, nullptr, out, nullptr, n);
+      }
+    }
+    if ((st = c.launch(a, 1, ndst))) return st;
+  }
+  return HCL_OK;
+}
+
+static void fill_fused(const Ctx& c, FusedArgs& f, const void* const* send, void* const* recv,
+                       uint64_t count, uint64_t B, int mode) {
+  memset(&f, 0, sizeof f);
+  for (int r = 0; r < c.W; ++r) {
+    f.src[r] = (const char*)send[r];
+    f.dst[r] = (char*)recv[r];
+    f.order[r] = (uint8_t)c.ring.order[r];
+    f.pos[r] = (uint8_t)c.ring.pos[r];
+  }
+  f.count = count;
+  f.B = B;
+  f.W = (uint32_t)c.W;
+  f.mode = (uint32_t)mode;
+}
+
+// plain copies send[r] -> recv[r] of n elements each, one launch
+static hcl_status_t copy_all(Ctx& c, const void* const* send, void* const* recv, uint64_t n) {
+  StepArgs a{};
+  for (int r = 0; r < c.W; ++r)
+    if (send[r] != recv[r]) add_seg(a, send[r], nullptr, recv[r], nullptr, n);
+  return c.launch(a, 1, 1);
+}
+
+extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* recv, int W, size_t count,
+                                          hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
+                                          const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
+  if (size_overflows(count, 1, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (count == 0) return c.finish();
+  if ((st = check_ptrs(send, recv, W, c.es))) return st;
+  int same = 0;
+  for (int r = 0; r < W; ++r) same += send[r] == recv[r];
+  if (same != 0 && same != W) return fail(HCL_ERR_ALIAS, "in-place All-Reduce needs recv[r] == send[r] for every rank");
+  const bool inplace = same == W;
+  const uint64_t bytes = count * c.es;
+  const BlockMap bm{count, ceil_div(count, (uint64_t)W)};
+  Inbox ib;
+  if ((st = get_inbox(c, bm.B, ib))) return st;
+  Range extra[1] = {{ib.base, ib.slot_bytes * 2 * W}};
+  if ((st = check_alias(send, recv, W, bytes, bytes, extra, ib.base ? 1 : 0, inplace, false))) return st;
+
+  if (W == 1) {
+    if ((st = copy_all(c, send, recv, count))) return st;
+    return c.finish();
+  }
+  if (c.sched == HCL_SCHED_FUSED) {
+    FusedArgs f;
+    fill_fused(c, f, send, recv, count, bm.B, 0);
+    if ((st = c.launch(f))) return st;
+    return c.finish();
+  }
+  char* part[kMaxRanks];
+  char* fin[kMaxRanks];
+  char* push[kMaxRanks];
+  const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
+  const bool fuse = c.fuse_rs_ag && !staged;
+  for (int r = 0; r < W; ++r) {
+    part[r] = (char*)recv[r];
+    fin[r] = off(recv[r], bm.lo(r), c.es);
+    push[r] = off(recv[c.ring.next(r)], bm.lo(r), c.es);
+  }
+  if ((st = run_rs(c, bm, send, part, send, fin, fuse ? push : nullptr, nullptr, 0, ib, /*forward_last=*/true))) return st;
+  if ((st = run_ag(c, bm, part, nullptr, fuse ? 1 : 0, ib, W - 1))) return st;
+  return c.finish();
+}
+
+extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* const* recv, int W, size_t recvcount,
+                                               hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
+                                               const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
+  if (size_overflows(recvcount, (uint64_t)W, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (recvcount == 0) return c.finish();
+  if ((st = check_ptrs(send, recv, W, c.es))) return st;
+  const uint64_t n = recvcount, es = c.es;
+  int same = 0;
+  for (int r = 0; r < W; ++r) same += (const char*)recv[r] == off(send[r], (uint64_t)r * n, es);
+  if (same != 0 && same != W) return fail(HCL_ERR_ALIAS, "in-place Reduce-Scatter needs recv[r] == send[r] + r * recvcount for every rank");
+  const bool inplace = same == W;
+  const BlockMap bm{n * W, n};
+  Inbox ib;
+  if ((st = get_inbox(c, n, ib))) return st;
+  const bool stepwise_direct = c.sched == HCL_SCHED_STEPWISE && c.xport == HCL_XPORT_DIRECT;
+  char* ws = nullptr;
+  uint64_t ws_slot = 0, ws_need = 0;
+  if (!inplace && stepwise_direct && W > 2) {
+    ws_slot = slot_bytes_for(n, es);
+    ws_need = ws_slot * 2 * W;
+    if (!opts || !opts->workspace) return fail(HCL_ERR_WORKSPACE, "out-of-place stepwise Reduce-Scatter needs opts->workspace (%llu bytes)", (unsigned long long)ws_need);
+    if (opts->workspace_bytes < ws_need) return fail(HCL_ERR_WORKSPACE, "workspace has %zu bytes, %llu needed", opts->workspace_bytes, (unsigned long long)ws_need);
+    if ((uintptr_t)opts->workspace % 16) return fail(HCL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    ws = (char*)opts->workspace;
+  }
+  Range extra[2] = {{ib.base, ib.slot_bytes * 2 * W}, {ws, ws_need}};
+  // a staged in-place ring never writes partials into send[], a direct one does
+  if ((st = check_alias(send, recv, W, n * W * es, n * es, extra, 2, inplace, inplace && stepwise_direct))) return st;
+
+  if (W == 1) {
+    if ((st = copy_all(c, send, recv, n))) return st;
+    return c.finish();
+  }
+  if (c.sched == HCL_SCHED_FUSED) {
+    FusedArgs f;
+    fill_fused(c, f, send, recv, n * W, n, 1);
+    if ((st = c.launch(f))) return st;
+    return c.finish();
+  }
+  char* part[kMaxRanks];
+  char* fin[kMaxRanks];
+  for (int r = 0; r < W; ++r) {
+    part[r] = inplace ? (char*)const_cast<void*>(send[r]) : nullptr;  // unused when ws or staged
+    fin[r] = (char*)recv[r];
+  }
+  if ((st = run_rs(c, bm, send, part, send, fin, nullptr, ws, ws_slot, ib, /*forward_last=*/false))) return st;
+  return c.finish();
+}
+
+extern "C" hcl_status_t hcl_all_gather_sim(const void* const* send, void* const* recv, int W, size_t sendcount,
+                                           hcl_dtype_t dtype, size_t chunk_bytes,
+                                           const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if (size_overflows(sendcount, (uint64_t)W, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (sendcount == 0) return c.finish();
+  if ((st = check_ptrs(send, recv, W, c.es))) return st;
+  const uint64_t n = sendcount, es = c.es;
+  int same = 0;
+  for (int r = 0; r < W; ++r) same += (const char*)send[r] == off((const void*)recv[r], (uint64_t)r * n, es);
+  if (same != 0 && same != W) return fail(HCL_ERR_ALIAS, "in-place All-Gather needs send[r] == recv[r] + r * sendcount for every rank");
+  const bool inplace = same == W;
+  const BlockMap bm{n * W, n};
+  Inbox ib;
+  if ((st = get_inbox(c, n, ib))) return st;
+  Range extra[1] = {{ib.base, ib.slot_bytes * 2 * W}};
+  if ((st = check_alias(send, recv, W, n * es, n * W * es, extra, 1, inplace, false))) return st;
+
+  if (c.sched == HCL_SCHED_FUSED) {
+    FusedArgs f;
+    fill_fused(c, f, send, recv, n * W, n, 2);
+    if ((st = c.launch(f))) return st;
+    return c.finish();
+  }
+  char* buf[kMaxRanks];
+  for (int r = 0; r < W; ++r) buf[r] = (char*)recv[r];
+  const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
+  if (staged && W > 1) {
+    // every rank puts its own block into its successor's inbox (and, out of
+    // place, into its own result)
+    StepArgs a{};
+    for (int k = 0; k < W; ++k) {
+      const int r = c.ring.order[k];
+      add_seg(a, send[r], nullptr, ib.slot(c.ring.next(r), 0), inplace ? nullptr : off(recv[r], bm.lo(r), es), n);
+    }
+    if ((st = c.launch(a, 1, inplace ? 1 : 2))) return st;
+  } else if (!inplace) {
+    // own block into own result
+    StepArgs a{};
+    for (int r = 0; r < W; ++r) add_seg(a, send[r], nullptr, off(recv[r], bm.lo(r), es), nullptr, n);
+    if ((st = c.launch(a, 1, 1))) return st;
+  }
+  if (W > 1) {
+    if ((st = run_ag(c, bm, buf, (inplace || staged) ? nullptr : send, 0, ib, 0))) return st;
+  }
+  return c.finish();
+}

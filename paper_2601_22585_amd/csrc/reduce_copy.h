@@ -1,0 +1,63 @@
+// Launch interface of the gfx950 reduce-copy kernels (host side sees only PODs).
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+namespace hcl {
+
+constexpr int kMaxSegs = 32;
+
+// One rank's work in one ring step: dst0[i] (and dst1[i]) = hop(src0[i], src1[i])
+// for NSRC = 2, or = src0[i] for NSRC = 1, i in [0, n).
+struct Seg {
+  const char* src0;  // incoming operand (predecessor's buffer or this rank's inbox)
+  const char* src1;  // local operand (NSRC = 2 only)
+  char* dst0;        // this rank's buffer
+  char* dst1;        // forwarded copy (NDST = 2 only)
+  uint64_t n;        // elements
+};
+
+// All ranks' segments of one step.  Tiles are ordered chunk-major: tile index
+// t -> (chunk j, segment d, tile k inside the chunk), j slowest.
+struct StepArgs {
+  Seg seg[kMaxSegs];
+  uint32_t nseg;
+  uint32_t tiles_per_chunk;
+  uint32_t total_tiles;
+  uint32_t pad_;
+  uint64_t chunk;  // elements per chunk (> 0)
+};
+
+// Whole-collective launch: every element's ring pass stays in one thread.
+struct FusedArgs {
+  const char* src[16];  // per rank, start of its full vector (AR, RS) or of its shard (AG)
+  char* dst[16];        // per rank, start of its full vector (AR, AG) or of its shard (RS)
+  uint8_t order[16];    // ring order
+  uint8_t pos[16];      // ring position of each rank
+  uint64_t count;       // elements in the full vector
+  uint64_t B;           // elements per block
+  uint64_t chunk;       // elements per chunk (> 0)
+  uint32_t tiles_per_chunk;
+  uint32_t total_tiles;
+  uint32_t W;
+  uint32_t mode;        // 0 All-Reduce, 1 Reduce-Scatter, 2 All-Gather
+};
+
+struct Tuning {
+  int threads;      // per workgroup, multiple of 64
+  int blocks;       // workgroups
+  int unroll;       // 1, 2, 4, 8
+  bool nontemporal;
+  bool vec;         // 128-bit path allowed (all addresses 16-byte aligned)
+};
+
+// Elements one tile covers for this dtype / tuning (vector path or not, same figure).
+uint64_t tile_elems(int dtype, const Tuning& t);
+// Unroll the fused kernel uses for a given W (fixed per W at compile time).
+int fused_unroll(int W);
+
+// Both return a hipError_t value (0 = success) from the launch.
+int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& t, void* stream);
+int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream);
+
+}  // namespace hcl

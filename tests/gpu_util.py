@@ -1,0 +1,130 @@
+"""Shared helpers of the GPU parity tests: run a collective through the C ABI
+binding and compare every output element with the CPU oracle's bits."""
+import numpy as np
+import torch
+
+import workloads as wl
+from oracle import ring_oracle as orc
+from paper_2601_22585_amd import hcl
+
+CODE = wl.DTYPE_CODE
+
+
+def device_inputs(cfg_id, W, count, dtype, dist, misalign=0):
+    """CPU-generated seeded inputs and their device copies.  misalign > 0 places
+    every device buffer `misalign` elements past a 256-byte aligned allocation."""
+    cpu = wl.make_inputs(cfg_id, W, count, dtype, dist)
+    dev = []
+    for t in cpu:
+        base = torch.empty(count + misalign + 64, dtype=t.dtype, device="cuda")
+        d = base[misalign:misalign + count]
+        d.copy_(t)
+        dev.append(d)
+    return cpu, dev
+
+
+def fresh(W, count, dtype, misalign=0, fill=None):
+    out = []
+    for _ in range(W):
+        base = torch.empty(count + misalign + 64, dtype=wl.TORCH_DTYPE[dtype], device="cuda")
+        d = base[misalign:misalign + count]
+        if fill is not None:
+            d.fill_(fill)
+        out.append(d)
+    return out
+
+
+def assert_same_bits(got_t, want_np, dtype, what):
+    got = wl.to_wire(got_t)
+    eq = wl.bits_equal_nan_aware(got, want_np, dtype)
+    if not eq.all():
+        bad = np.flatnonzero(~eq)
+        i = int(bad[0])
+        raise AssertionError(f"{what}: {bad.size} of {got.size} elements differ; first at {i}: "
+                             f"got {got[i]!r} want {want_np[i]!r}")
+
+
+def pinned_stage(nbytes):
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, pin_memory=True)
+
+
+def run_allreduce(cfg_id, W, count, dtype, dist, ring=None, chunk_bytes=0, inplace=False, misalign=0,
+                  cpu_inputs=None, **opt):
+    """Runs hcl_allreduce_sim and checks all W outputs against the oracle.  Returns launches."""
+    if cpu_inputs is None:
+        cpu, dev = device_inputs(cfg_id, W, count, dtype, dist, misalign)
+    else:
+        cpu = cpu_inputs
+        dev = []
+        for t in cpu:
+            base = torch.empty(count + misalign + 64, dtype=t.dtype, device="cuda")
+            d = base[misalign:misalign + count]
+            d.copy_(t)
+            dev.append(d)
+    es = wl.ESIZE[dtype]
+    want = orc.allreduce([wl.to_wire(t) for t in cpu], CODE[dtype], ring=ring,
+                         chunk_elems=chunk_bytes // es)
+    if opt.get("xport") == "host_staged":
+        opt["host_stage"] = pinned_stage(hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, W, count, CODE[dtype],
+                                                              chunk_bytes, xport="host_staged"))
+    recv = dev if inplace else fresh(W, count, dtype, misalign, fill=0)
+    n = hcl.allreduce_sim(dev, recv, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"allreduce W={W} count={count} {dtype} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt}"
+    for r in range(W):
+        assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+        if not inplace:
+            assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    return n
+
+
+def run_reduce_scatter(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, inplace=False, misalign=0, **opt):
+    cpu, dev = device_inputs(cfg_id, W, W * n, dtype, dist, misalign)
+    es = wl.ESIZE[dtype]
+    want = orc.reduce_scatter([wl.to_wire(t) for t in cpu], CODE[dtype], ring=ring, chunk_elems=chunk_bytes // es)
+    if opt.get("xport") == "host_staged":
+        opt["host_stage"] = pinned_stage(hcl.host_stage_bytes(hcl.KIND_REDUCE_SCATTER, W, n, CODE[dtype],
+                                                              chunk_bytes, xport="host_staged"))
+    if inplace:
+        recv = [dev[r][r * n:(r + 1) * n] for r in range(W)]
+    else:
+        recv = fresh(W, n, dtype, misalign, fill=0)
+        wsb = hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, CODE[dtype], chunk_bytes,
+                                  sched=opt.get("sched", "stepwise"), xport=opt.get("xport", "direct"))
+        if wsb:
+            opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    nl = hcl.reduce_scatter_sim(dev, recv, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"reduce_scatter W={W} n={n} {dtype} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')} {opt.get('xport')}"
+    for r in range(W):
+        assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+        if not inplace:
+            assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    return nl
+
+
+def run_all_gather(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, inplace=False, misalign=0, **opt):
+    cpu = wl.make_inputs(cfg_id, W, n, dtype, dist)
+    es = wl.ESIZE[dtype]
+    want = orc.all_gather([wl.to_wire(t) for t in cpu], CODE[dtype], ring=ring, chunk_elems=chunk_bytes // es)
+    if opt.get("xport") == "host_staged":
+        opt["host_stage"] = pinned_stage(hcl.host_stage_bytes(hcl.KIND_ALL_GATHER, W, n, CODE[dtype],
+                                                              chunk_bytes, xport="host_staged"))
+    recv = fresh(W, W * n, dtype, misalign, fill=0)
+    if inplace:
+        send = [recv[r][r * n:(r + 1) * n] for r in range(W)]
+        for r in range(W):
+            send[r].copy_(cpu[r])
+    else:
+        send = []
+        for t in cpu:
+            base = torch.empty(n + misalign + 64, dtype=t.dtype, device="cuda")
+            d = base[misalign:misalign + n]
+            d.copy_(t)
+            send.append(d)
+    nl = hcl.all_gather_sim(send, recv, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"all_gather W={W} n={n} {dtype} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')} {opt.get('xport')}"
+    for r in range(W):
+        assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+    return nl
