@@ -8,8 +8,11 @@ that are already resident in HBM.  Prints ONE JSON line:
   value        S / t in GB/s  (S = bytes per rank buffer: the collective's
                algorithm bandwidth with one GPU doing all W ranks' work)
   roofline     the dominant kernel's algorithmic HBM bytes per launch divided
-               by its average launch duration (HIP events recorded around every
-               launch on the stream the launches run on), against 8 TB/s
+               by its average launch duration, against 8 TB/s.  The duration
+               comes from HIP events the library records, inside the timed
+               region and on the stream the launches run on, around each phase
+               of a step (Reduce-Scatter launches, All-Gather launches); with
+               --per-launch-events around every single launch instead
   cpu_baseline the CPU oracle timed on a bounded sample of the same workload
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
@@ -64,13 +67,15 @@ def main():
     ap.add_argument("--fuse-rs-ag", action="store_true")
     ap.add_argument("--inplace", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-events", action="store_true", help="do not bracket single launches with events")
+    ap.add_argument("--no-events", action="store_true", help="record no events inside the timed region")
+    ap.add_argument("--per-launch-events", action="store_true",
+                    help="bracket every launch (about 3 us each) instead of each phase")
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--blocks", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=0)
     ap.add_argument("--chunk-bytes", type=int, default=-1)
-    ap.add_argument("--cpu-sample-div", type=int, default=2, help="oracle sample = 1/div of every block")
+    ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle sample = leading 1/div of every block")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -118,15 +123,26 @@ def main():
         from oracle import ring_oracle as orc
         assert count % W == 0, "the sampled replay assumes equal blocks"
         work = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in sample_idx]) for r in range(W)]
-        threads = orc.set_threads(0)
+        ce = min(chunk_bytes // es, m) if chunk_bytes else 0
+        # one thread first, on an eighth of the sample, then every host core on all of it
+        m1 = max(1, m // 8)
+        small = [np.concatenate([w[c * m:c * m + m1] for c in range(W)]) for w in work]
+        orc.set_threads(1)
         t0 = time.perf_counter()
-        orc.allreduce_inplace(work, wl.DTYPE_CODE[dtype], chunk_elems=min(chunk_bytes // es, m) if chunk_bytes else 0)
+        orc.allreduce_inplace(small, wl.DTYPE_CODE[dtype], chunk_elems=min(ce, m1))
+        t_one = time.perf_counter() - t0
+        del small
+        threads = orc.set_threads(os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        orc.allreduce_inplace(work, wl.DTYPE_CODE[dtype], chunk_elems=ce)
         t_cpu = time.perf_counter() - t0
         sample_bytes = W * m * es
         cpu_baseline = {"value": round(sample_bytes / t_cpu / 1e9, 6), "unit": "GB/s", "cores": threads, "kind": "oracle",
                         "sample": f"leading {m} of {B} elements of each of the {W} blocks of all {W} rank buffers "
                                   f"({sample_bytes / 2**20:.0f} MiB per rank), ring replayed in {t_cpu:.2f} s",
-                        "seconds": round(t_cpu, 3)}
+                        "seconds": round(t_cpu, 3),
+                        "one_thread": {"value": round(W * m1 * es / t_one / 1e9, 6), "unit": "GB/s",
+                                       "sample_MiB_per_rank": round(W * m1 * es / 2**20, 1), "seconds": round(t_one, 3)}}
 
     # ---- warm-up (the first run is also checked against the oracle sample) ----
     for i in range(max(1, args.warmup)):
@@ -147,7 +163,9 @@ def main():
 
     # ---- timed region: exactly K steps ----
     K = args.steps
-    per = launches + 1
+    phase_mode = not args.per_launch_events
+    n_phases = 1 if args.sched == "fused" else 2
+    per = (n_phases if phase_mode else launches) + 1
     ev = None if args.no_events else hcl.EventList(K * per)
     stream = torch.cuda.current_stream()
     torch.cuda.synchronize()
@@ -156,38 +174,53 @@ def main():
         o = dict(opt)
         if ev is not None:
             o["events"] = (ev, k * per, per)
+            o["events_per_phase"] = phase_mode
         hcl.allreduce_sim(send, recv, chunk_bytes=chunk_bytes, stream=stream, **o)
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = t_total / K * 1e3
 
-    # ---- per-launch durations of the dominant kernel ----
+    # ---- average launch duration of the dominant kernel ----
+    staged = xport == "host_staged"
+    fuse = args.fuse_rs_ag and not staged
     if args.sched == "fused":
         kernel = f"ring_fused_vec<{dtype},W={W}>"
-        dom = [0]
-        bytes_per_launch = 2 * W * S
+        bytes_per_launch = 2 * W * S          # every rank's vector read once, written once
         call_bytes = 2 * W * S
+        n_dom = 1                              # launches of the dominant kernel per step
+        dom = [0]                              # their indices among a step's launches
     else:
-        # Reduce-Scatter launches: 2 reads + 1 write of one block per rank = 3 * S bytes
-        staged = xport == "host_staged"
-        first_rs = 1 if staged else 0
-        n_rs = W - 1
-        if args.fuse_rs_ag and not staged:
-            n_rs -= 1      # the last RS step is the <2,2> variant; count only the plain ones
-        dom = list(range(first_rs, first_rs + n_rs))
+        # a Reduce-Scatter launch reads two blocks and writes one per rank: 3 * S bytes
         kernel = f"reduce_copy_vec<{dtype},NSRC=2,NDST=1>"
         bytes_per_launch = 3 * S
-        call_bytes = 5 * (W - 1) * S - (S if (args.fuse_rs_ag and not staged) else 0)
+        call_bytes = 5 * (W - 1) * S - (S if fuse else 0)
+        first_rs = 1 if staged else 0
+        n_dom = W - 1
+        dom = list(range(first_rs, first_rs + n_dom))
     roof = None
     if ev is not None:
-        durs = [ev.elapsed_ms(k * per + i, k * per + i + 1) for k in range(K) for i in dom]
-        avg_ms = sum(durs) / len(durs)
+        if phase_mode:
+            # phase 0 holds the W-1 Reduce-Scatter launches (the fused last one, 4/3 of the bytes of a
+            # plain one, and the staged pre-step are counted by their share of bytes)
+            rs_ms = [ev.elapsed_ms(k * per, k * per + 1) for k in range(K)]
+            if args.sched == "fused":
+                units = 1.0
+            else:
+                units = (W - 1) + (1.0 / 3.0 if fuse else 0.0) + (2.0 / 3.0 if staged else 0.0)
+            avg_ms = sum(rs_ms) / len(rs_ms) / units
+            timed = K * n_dom
+            how = "phase events: (time of the phase's launches, gaps included) / launches"
+        else:
+            durs = [ev.elapsed_ms(k * per + i, k * per + i + 1) for k in range(K) for i in dom]
+            avg_ms = sum(durs) / len(durs)
+            timed = len(durs)
+            how = "one event pair per launch"
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        workload = cfg["name"]
         roof = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(kernel, workload),
-                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches_timed": len(durs)}
-        if xport == "host_staged":
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(kernel, cfg["name"]),
+                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches_timed": timed,
+                "timing": how}
+        if staged:
             roof["note"] = "staged transport: the link to host memory, not HBM, bounds this path"
         ev.close()
 

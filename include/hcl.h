@@ -95,7 +95,8 @@ typedef struct hcl_opts {
   void *host_stage;        /* pinned host inboxes; see hcl_host_stage_bytes                 */
   size_t host_stage_bytes;
   int threads;             /* threads per workgroup: 0 = default, else 64..1024, multiple of 64 */
-  int blocks;              /* workgroups per launch: 0 = default (a multiple of the CU count)   */
+  int blocks;              /* workgroups per launch: 0 = default (one tile per workgroup); smaller
+                              values give a persistent grid striding over the tiles            */
   int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default, 1, 2, 4 or 8 */
   int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
@@ -105,6 +106,10 @@ typedef struct hcl_opts {
                               recorded on the stream before launch k, and one more after the
                               last launch; launches beyond n_events-1 are not bracketed     */
   int n_events;
+  int events_per_phase;    /* 0: as above.  1: events only at phase boundaries -- event 0 before the
+                              first Reduce-Scatter launch (or the only phase of the call), event 1
+                              before the first All-Gather launch of an All-Reduce, the next one
+                              after the last launch: the cheap way to time a phase's launches   */
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
 } hcl_opts_t;
 

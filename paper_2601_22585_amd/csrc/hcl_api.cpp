@@ -207,6 +207,8 @@ struct Ctx {
   const hcl_opts_t* opts = nullptr;
   void* stream = nullptr;
   int launches = 0;
+  bool phase_events = false;  // events at phase boundaries instead of around every launch
+  int phases = 0;
 
   hcl_status_t init(int W_, hcl_dtype_t dt, size_t chunk_bytes, const hcl_opts_t* o, void* st) {
     opts = o;
@@ -228,6 +230,7 @@ struct Ctx {
     fuse_rs_ag = o && o->fuse_rs_ag;
     if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
     if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
+    phase_events = o && o->events_per_phase;
 
     int threads = o && o->threads ? o->threads : env_int("HCL_THREADS", 0);
     int unroll = o && o->unroll ? o->unroll : env_int("HCL_UNROLL", 0);
@@ -247,17 +250,20 @@ struct Ctx {
     return HCL_OK;
   }
 
-  int grid_for(uint32_t total_tiles) {
-    int cap = max_blocks;
-    if (cap == 0) {
-      int cus = hcl_device_cu_count();
-      if (cus <= 0) cus = 256;
-      cap = cus * (2048 / tune.threads);  // fill every CU's wave slots
-    }
-    return total_tiles < (uint32_t)cap ? (int)total_tiles : cap;
+  // Default: one tile per workgroup, which measured faster on MI355X than a
+  // persistent grid; opts->blocks caps the grid and the kernels then stride.
+  int grid_for(uint32_t total_tiles) const {
+    const uint32_t cap = max_blocks ? (uint32_t)max_blocks : 0x7FFFFFFFu;
+    return (int)(total_tiles < cap ? total_tiles : cap);
   }
 
-  hcl_status_t mark(int idx) {
+  // start of a phase (Reduce-Scatter steps, All-Gather steps, or the single fused launch)
+  hcl_status_t phase() {
+    if (!phase_events) return HCL_OK;
+    return record(phases++);
+  }
+  hcl_status_t mark(int idx) { return phase_events ? HCL_OK : record(idx); }
+  hcl_status_t record(int idx) {
     if (opts && opts->events && idx < opts->n_events) {
       hipError_t rc = hipEventRecord((hipEvent_t)opts->events[idx], (hipStream_t)stream);
       if (rc != hipSuccess) return fail(HCL_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(rc));
@@ -327,7 +333,8 @@ struct Ctx {
   }
 
   hcl_status_t finish() {
-    hcl_status_t st = launches ? mark(launches) : HCL_OK;
+    hcl_status_t st = HCL_OK;
+    if (launches) st = phase_events ? record(phases) : record(launches);
     if (opts && opts->n_launches) *opts->n_launches = launches;
     return st;
   }
@@ -580,12 +587,14 @@ extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* 
   if ((st = check_alias(send, recv, W, bytes, bytes, extra, ib.base ? 1 : 0, inplace, false))) return st;
 
   if (W == 1) {
+    if ((st = c.phase())) return st;
     if ((st = copy_all(c, send, recv, count))) return st;
     return c.finish();
   }
   if (c.sched == HCL_SCHED_FUSED) {
     FusedArgs f;
     fill_fused(c, f, send, recv, count, bm.B, 0);
+    if ((st = c.phase())) return st;
     if ((st = c.launch(f))) return st;
     return c.finish();
   }
@@ -599,7 +608,9 @@ extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* 
     fin[r] = off(recv[r], bm.lo(r), c.es);
     push[r] = off(recv[c.ring.next(r)], bm.lo(r), c.es);
   }
+  if ((st = c.phase())) return st;
   if ((st = run_rs(c, bm, send, part, send, fin, fuse ? push : nullptr, nullptr, 0, ib, /*forward_last=*/true))) return st;
+  if ((st = c.phase())) return st;
   if ((st = run_ag(c, bm, part, nullptr, fuse ? 1 : 0, ib, W - 1))) return st;
   return c.finish();
 }
@@ -638,12 +649,14 @@ extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* co
   if ((st = check_alias(send, recv, W, n * W * es, n * es, extra, 2, inplace, inplace && stepwise_direct))) return st;
 
   if (W == 1) {
+    if ((st = c.phase())) return st;
     if ((st = copy_all(c, send, recv, n))) return st;
     return c.finish();
   }
   if (c.sched == HCL_SCHED_FUSED) {
     FusedArgs f;
     fill_fused(c, f, send, recv, n * W, n, 1);
+    if ((st = c.phase())) return st;
     if ((st = c.launch(f))) return st;
     return c.finish();
   }
@@ -653,6 +666,7 @@ extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* co
     part[r] = inplace ? (char*)const_cast<void*>(send[r]) : nullptr;  // unused when ws or staged
     fin[r] = (char*)recv[r];
   }
+  if ((st = c.phase())) return st;
   if ((st = run_rs(c, bm, send, part, send, fin, nullptr, ws, ws_slot, ib, /*forward_last=*/false))) return st;
   return c.finish();
 }
@@ -680,12 +694,14 @@ extern "C" hcl_status_t hcl_all_gather_sim(const void* const* send, void* const*
   if (c.sched == HCL_SCHED_FUSED) {
     FusedArgs f;
     fill_fused(c, f, send, recv, n * W, n, 2);
+    if ((st = c.phase())) return st;
     if ((st = c.launch(f))) return st;
     return c.finish();
   }
   char* buf[kMaxRanks];
   for (int r = 0; r < W; ++r) buf[r] = (char*)recv[r];
   const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
+  if ((st = c.phase())) return st;
   if (staged && W > 1) {
     // every rank puts its own block into its successor's inbox (and, out of
     // place, into its own result)

@@ -56,6 +56,7 @@ class Opts(ctypes.Structure):
         ("fuse_rs_ag", ctypes.c_int),
         ("events", ctypes.POINTER(ctypes.c_void_p)),
         ("n_events", ctypes.c_int),
+        ("events_per_phase", ctypes.c_int),
         ("n_launches", ctypes.POINTER(ctypes.c_int)),
     ]
 
@@ -155,7 +156,8 @@ class EventList:
 
 
 def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, host_stage=None,
-              threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None):
+              threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None,
+              events_per_phase=False):
     """Builds the hcl_opts_t struct.  Returns (opts, keepalive): keep `keepalive`
     referenced until the call has returned."""
     o = Opts()
@@ -183,6 +185,7 @@ def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, ho
         o.events = ctypes.cast(ctypes.byref(ev.arr, first * ctypes.sizeof(ctypes.c_void_p)),
                                ctypes.POINTER(ctypes.c_void_p))
         o.n_events = n
+        o.events_per_phase = 1 if events_per_phase else 0
         keep.append(ev)
     nl = ctypes.c_int(0)
     o.n_launches = ctypes.pointer(nl)
