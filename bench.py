@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
-"""Benchmark of the ring All-Reduce hot path on one MI355X.
+"""Benchmark of the ring collectives' hot path on one MI355X.
 
-One "step" is one complete ring All-Reduce (every Reduce-Scatter and All-Gather
-step of all W simulated ranks) over one batch of seeded synthetic rank buffers
-that are already resident in HBM.  Prints ONE JSON line:
+Default run: one "step" is one complete ring All-Reduce (every Reduce-Scatter
+and All-Gather step of all W simulated ranks) of the headline workload -- W = 8
+ranks, 256 MiB of bf16 per rank, 4 MiB chunks -- over seeded synthetic rank
+buffers that are already resident in HBM.  Prints ONE JSON line:
 
   value        S / t in GB/s  (S = bytes per rank buffer: the collective's
                algorithm bandwidth with one GPU doing all W ranks' work)
@@ -13,10 +14,15 @@ that are already resident in HBM.  Prints ONE JSON line:
                region and on the stream the launches run on, around each phase
                of a step (Reduce-Scatter launches, All-Gather launches); with
                --per-launch-events around every single launch instead
-  cpu_baseline the CPU oracle timed on a bounded sample of the same workload
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload,
+               whose result is also bit-compared with the GPU's first run
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
-                       [--sched stepwise|fused] [--fuse-rs-ag] [--no-cpu-baseline]
+Other workloads (reported in the design doc, not bench lines of their own):
+  --config 1            4 ranks, 1 MiB fp32
+  --config 3 --bytes-per-rank N   fp16, 16 ranks, message-size sweep point
+  --config 4 | 41       ZeRO-style Reduce-Scatter then All-Gather, bf16 | int32,
+                        --shard-elems to scale the 2 GiB shards down
+  --config 5            host-staged All-Reduce, 512 MiB fp32 per rank
 """
 import argparse
 import hashlib
@@ -57,16 +63,22 @@ def stored_traffic(kernel, workload):
     return None
 
 
-def main():
+def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 5])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 41, 5])
+    ap.add_argument("--op", default=None, choices=["allreduce", "reduce_scatter", "all_gather"],
+                    help="collective to time (default: the config's; config 4 times reduce_scatter unless told otherwise)")
     ap.add_argument("--sched", default="stepwise", choices=["stepwise", "fused"])
     ap.add_argument("--fuse-rs-ag", action="store_true")
     ap.add_argument("--inplace", action="store_true")
+    ap.add_argument("--bytes-per-rank", type=int, default=0, help="config 3: bytes per rank buffer")
+    ap.add_argument("--shard-elems", type=int, default=0, help="config 4: elements per shard (default 2 GiB worth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=1 << 24,
+                    help="oracle sample: at most this many leading elements of every block")
     ap.add_argument("--no-events", action="store_true", help="record no events inside the timed region")
     ap.add_argument("--per-launch-events", action="store_true",
                     help="bracket every launch (about 3 us each) instead of each phase")
@@ -75,9 +87,11 @@ def main():
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=0)
     ap.add_argument("--chunk-bytes", type=int, default=-1)
-    ap.add_argument("--cpu-sample-div", type=int, default=1, help="oracle sample = leading 1/div of every block")
-    args = ap.parse_args()
+    return ap.parse_args()
 
+
+def main():
+    args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU: all W ranks are simulated in one MI355X's memory; "
               "--gpus must be 1", file=sys.stderr)
@@ -91,82 +105,145 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    hcl.lib()
+    hcl.lib()   # raises if the HIP library has not been built: there is no fallback
 
-    cfg = wl.CONFIGS[args.config]
-    W, dtype, count = cfg["W"], cfg["dtype"], cfg["count"]
+    cfg = dict(wl.CONFIGS[args.config])
+    W, dtype = cfg["W"], cfg["dtype"]
     es = wl.ESIZE[dtype]
-    chunk_bytes = cfg["chunk_bytes"] if args.chunk_bytes < 0 else args.chunk_bytes
+    code = wl.DTYPE_CODE[dtype]
     xport = cfg.get("xport", "direct")
-    S = count * es
-    B = -(-count // W)
+    op = args.op or ("reduce_scatter" if cfg["op"] == "rs+ag" else "allreduce")
+    name = cfg["name"]
+    if args.config == 3:
+        nbytes = args.bytes_per_rank or (256 << 20)
+        count = nbytes // es
+        name = f"{name}_{nbytes}B"
+        chunk_default = min(-(-count // W) * es, cfg["chunk_bytes"])
+    elif args.config in (4, 41):
+        shard = args.shard_elems or cfg["count"] // W
+        count = shard * W
+        if args.shard_elems:
+            name = f"{name}_shard{shard}"
+        chunk_default = cfg["chunk_bytes"]
+    else:
+        count = cfg["count"]
+        chunk_default = cfg["chunk_bytes"]
+    chunk_bytes = chunk_default if args.chunk_bytes < 0 else args.chunk_bytes
+    S = count * es                 # bytes of a full vector (per rank)
+    B = -(-count // W)             # elements per block
+    if op != "allreduce":
+        assert count % W == 0
+        name = f"{name}:{op}"
 
-    # seeded inputs, generated on the device
-    send = [torch.empty(count, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
-    for r in range(W):
-        wl.fill_rank(send[r], wl.rank_seed(args.config, r), cfg["dist"])
-    recv = send if args.inplace else [torch.empty_like(t) for t in send]
+    # ---- buffers: seeded inputs generated on the device ----
+    def new(n):
+        return torch.empty(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda")
+
     opt = dict(sched=args.sched, xport=xport, threads=args.threads, blocks=args.blocks, unroll=args.unroll,
-               nontemporal=args.nontemporal, fuse_rs_ag=args.fuse_rs_ag)
-    stage = None
+               nontemporal=args.nontemporal)
+    if op == "allreduce":
+        opt["fuse_rs_ag"] = args.fuse_rs_ag
+        send = [new(count) for _ in range(W)]
+        recv = send if args.inplace else [new(count) for _ in range(W)]
+        kind = hcl.KIND_ALLREDUCE
+        call = hcl.allreduce_sim
+        per_call_count = count
+    elif op == "reduce_scatter":
+        send = [new(count) for _ in range(W)]
+        recv = [send[r][r * B:(r + 1) * B] for r in range(W)] if args.inplace else [new(B) for _ in range(W)]
+        kind = hcl.KIND_REDUCE_SCATTER
+        call = hcl.reduce_scatter_sim
+        per_call_count = B
+        if not args.inplace:
+            wsb = hcl.workspace_bytes(kind, W, B, code, chunk_bytes, sched=args.sched, xport=xport)
+            if wsb:
+                opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    else:
+        recv = [new(count) for _ in range(W)]
+        send = [recv[r][r * B:(r + 1) * B] for r in range(W)] if args.inplace else [new(B) for _ in range(W)]
+        kind = hcl.KIND_ALL_GATHER
+        call = hcl.all_gather_sim
+        per_call_count = B
+
+    def refill():
+        for r in range(W):
+            wl.fill_rank(send[r], wl.rank_seed(args.config, r), cfg["dist"])
+
+    refill()
     if xport == "host_staged":
-        nb = hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, W, count, wl.DTYPE_CODE[dtype], chunk_bytes, xport=xport)
-        stage = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
-        opt["host_stage"] = stage
+        nb = hcl.host_stage_bytes(kind, W, per_call_count, code, chunk_bytes, xport=xport)
+        opt["host_stage"] = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
     torch.cuda.synchronize()
 
-    # ---- CPU oracle on a bounded sample (also the parity check of the first run) ----
+    # ---- CPU oracle on a bounded sample: leading m elements of every block ----
     cpu_baseline = None
-    m = max(1, B // max(1, args.cpu_sample_div))           # leading m elements of every block
-    sample_idx = [(min(c * B, count), min(min(c * B, count) + m, min((c + 1) * B, count))) for c in range(W)]
+    m = min(B, max(1, args.cpu_sample_elems))
+    win = [(min(c * B, count), min(min(c * B, count) + m, min((c + 1) * B, count))) for c in range(W)]
+    want = None
     if not args.no_cpu_baseline:
         from oracle import ring_oracle as orc
         assert count % W == 0, "the sampled replay assumes equal blocks"
-        work = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in sample_idx]) for r in range(W)]
         ce = min(chunk_bytes // es, m) if chunk_bytes else 0
+        if op == "all_gather":
+            ins = [wl.to_wire(send[r][:m]) for r in range(W)]
+        else:
+            ins = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in win]) for r in range(W)]
+        fn = {"allreduce": orc.allreduce, "reduce_scatter": orc.reduce_scatter, "all_gather": orc.all_gather}[op]
         # one thread first, on an eighth of the sample, then every host core on all of it
         m1 = max(1, m // 8)
-        small = [np.concatenate([w[c * m:c * m + m1] for c in range(W)]) for w in work]
+        if op == "all_gather":
+            small = [a[:m1] for a in ins]
+        else:
+            small = [np.concatenate([a[c * m:c * m + m1] for c in range(W)]) for a in ins]
         orc.set_threads(1)
         t0 = time.perf_counter()
-        orc.allreduce_inplace(small, wl.DTYPE_CODE[dtype], chunk_elems=min(ce, m1))
+        fn(small, code, chunk_elems=min(ce, m1))
         t_one = time.perf_counter() - t0
         del small
         threads = orc.set_threads(os.cpu_count() or 1)
         t0 = time.perf_counter()
-        orc.allreduce_inplace(work, wl.DTYPE_CODE[dtype], chunk_elems=ce)
+        want = fn(ins, code, chunk_elems=ce)
         t_cpu = time.perf_counter() - t0
-        sample_bytes = W * m * es
+        del ins
+        sample_bytes = W * m * es      # bytes of the sampled full vector, per rank
         cpu_baseline = {"value": round(sample_bytes / t_cpu / 1e9, 6), "unit": "GB/s", "cores": threads, "kind": "oracle",
-                        "sample": f"leading {m} of {B} elements of each of the {W} blocks of all {W} rank buffers "
-                                  f"({sample_bytes / 2**20:.0f} MiB per rank), ring replayed in {t_cpu:.2f} s",
+                        "sample": f"{op}: leading {m} of {B} elements of each of the {W} blocks of every rank "
+                                  f"({sample_bytes / 2**20:.1f} MiB of vector per rank), replayed in {t_cpu:.2f} s "
+                                  f"(input copies included)",
                         "seconds": round(t_cpu, 3),
                         "one_thread": {"value": round(W * m1 * es / t_one / 1e9, 6), "unit": "GB/s",
-                                       "sample_MiB_per_rank": round(W * m1 * es / 2**20, 1), "seconds": round(t_one, 3)}}
+                                       "sample_MiB_per_rank": round(W * m1 * es / 2**20, 2), "seconds": round(t_one, 3)}}
+
+    def check_first_run():
+        for r in range(W):
+            if op == "reduce_scatter":
+                got = wl.to_wire(recv[r][:m])
+            else:
+                got = np.concatenate([wl.to_wire(recv[r][lo:hi]) for lo, hi in win])
+            if not wl.bits_equal_nan_aware(got, want[r], dtype).all():
+                raise SystemExit(f"bench.py: {op}: rank {r} differs from the CPU oracle on the sampled elements")
+        cpu_baseline["parity"] = "bit-exact on the sample"
 
     # ---- warm-up (the first run is also checked against the oracle sample) ----
+    clobbers = args.inplace and op != "all_gather"
+    launches = 0
     for i in range(max(1, args.warmup)):
-        launches = hcl.allreduce_sim(send, recv, chunk_bytes=chunk_bytes, **opt)
+        launches = call(send, recv, chunk_bytes=chunk_bytes, **opt)
         if i == 0:
             torch.cuda.synchronize()
-            if cpu_baseline is not None:
-                for r in range(W):
-                    got = np.concatenate([wl.to_wire(recv[r][lo:hi]) for lo, hi in sample_idx])
-                    if not wl.bits_equal_nan_aware(got, work[r], dtype).all():
-                        raise SystemExit(f"bench.py: rank {r} differs from the CPU oracle on the sampled elements")
-                cpu_baseline["parity"] = "bit-exact on the sample"
-                del work
-            if args.inplace:   # keep values bounded: refill before timing
-                for r in range(W):
-                    wl.fill_rank(send[r], wl.rank_seed(args.config, r), cfg["dist"])
+            if want is not None:
+                check_first_run()
+                want = None
+            if clobbers:   # in-place sums overwrite their inputs: start the timed runs from fresh values
+                refill()
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps ----
     K = args.steps
     phase_mode = not args.per_launch_events
-    n_phases = 1 if args.sched == "fused" else 2
+    n_phases = 2 if (op == "allreduce" and args.sched == "stepwise" and W > 1) else 1
     per = (n_phases if phase_mode else launches) + 1
-    ev = None if args.no_events else hcl.EventList(K * per)
+    ev = None if (args.no_events or launches == 0) else hcl.EventList(K * per)
     stream = torch.cuda.current_stream()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -175,41 +252,47 @@ def main():
         if ev is not None:
             o["events"] = (ev, k * per, per)
             o["events_per_phase"] = phase_mode
-        hcl.allreduce_sim(send, recv, chunk_bytes=chunk_bytes, stream=stream, **o)
+        call(send, recv, chunk_bytes=chunk_bytes, stream=stream, **o)
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = t_total / K * 1e3
 
-    # ---- average launch duration of the dominant kernel ----
+    # ---- algorithmic bytes: of the whole call, and of one launch of the dominant kernel ----
     staged = xport == "host_staged"
-    fuse = args.fuse_rs_ag and not staged
+    fuse = bool(opt.get("fuse_rs_ag")) and not staged
     if args.sched == "fused":
-        kernel = f"ring_fused_vec<{dtype},W={W}>"
-        bytes_per_launch = 2 * W * S          # every rank's vector read once, written once
-        call_bytes = 2 * W * S
-        n_dom = 1                              # launches of the dominant kernel per step
-        dom = [0]                              # their indices among a step's launches
+        kernel = f"ring_fused_vec<{dtype},W={W}>" if op != "all_gather" else "gather_fused_vec"
+        call_bytes = {"allreduce": 2 * W * S, "reduce_scatter": (W + 1) * S, "all_gather": (W + 1) * S}[op]
+        bytes_per_launch, n_dom, dom, units = call_bytes, 1, [0], 1.0
+    elif op == "all_gather":
+        kernel = "reduce_copy_vec<copy,NSRC=1,NDST=1>"
+        # a step copies one block per rank: S bytes read and S written, all ranks together; out of
+        # place, every rank also copies its own shard into its result, which is one more such launch
+        own_copy = 0 if args.inplace else 2 * S
+        call_bytes = 2 * (W - 1) * S + own_copy
+        bytes_per_launch = 2 * S
+        n_dom, dom = W - 1, list(range(0 if args.inplace else 1, launches))
+        units = (W - 1) + (0 if args.inplace else 1)
     else:
         # a Reduce-Scatter launch reads two blocks and writes one per rank: 3 * S bytes
         kernel = f"reduce_copy_vec<{dtype},NSRC=2,NDST=1>"
         bytes_per_launch = 3 * S
-        call_bytes = 5 * (W - 1) * S - (S if fuse else 0)
         first_rs = 1 if staged else 0
         n_dom = W - 1
         dom = list(range(first_rs, first_rs + n_dom))
+        units = (W - 1) + (1.0 / 3.0 if fuse else 0.0) + (2.0 / 3.0 if staged else 0.0)
+        call_bytes = 3 * (W - 1) * S
+        if op == "allreduce":
+            call_bytes = 5 * (W - 1) * S - (S if fuse else 0)
     roof = None
     if ev is not None:
         if phase_mode:
-            # phase 0 holds the W-1 Reduce-Scatter launches (the fused last one, 4/3 of the bytes of a
-            # plain one, and the staged pre-step are counted by their share of bytes)
-            rs_ms = [ev.elapsed_ms(k * per, k * per + 1) for k in range(K)]
-            if args.sched == "fused":
-                units = 1.0
-            else:
-                units = (W - 1) + (1.0 / 3.0 if fuse else 0.0) + (2.0 / 3.0 if staged else 0.0)
-            avg_ms = sum(rs_ms) / len(rs_ms) / units
+            # phase 0 holds the dominant kernel's launches; launches of another shape in the same
+            # phase (fused last RS step, staged pre-step, own-shard copy) count by their share of bytes
+            ph = [ev.elapsed_ms(k * per, k * per + 1) for k in range(K)]
+            avg_ms = sum(ph) / len(ph) / units
             timed = K * n_dom
-            how = "phase events: (time of the phase's launches, gaps included) / launches"
+            how = "phase events: (duration of the phase's launches, gaps included) / launches"
         else:
             durs = [ev.elapsed_ms(k * per + i, k * per + i + 1) for k in range(K) for i in dom]
             avg_ms = sum(durs) / len(durs)
@@ -217,21 +300,25 @@ def main():
             how = "one event pair per launch"
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(kernel, cfg["name"]),
-                "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches_timed": timed,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(kernel, name),
+                "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_ms, 5), "launches_timed": timed,
                 "timing": how}
         if staged:
-            roof["note"] = "staged transport: the link to host memory, not HBM, bounds this path"
+            # every block that travels is written to host memory once and read back once
+            link = (2 * (W - 1) if op == "allreduce" else (W - 1)) * S
+            roof["note"] = "staged transport: the host link, not HBM, bounds this path"
+            roof["link_GBps_each_way"] = round(link / (ms_per_step * 1e-3) / 1e9, 2)
         ev.close()
 
     value = S / (ms_per_step * 1e-3) / 1e9
     out = {
-        "metric": "ring all-reduce algorithm GB/s on 1 MI355X",
+        "metric": "ring all-reduce algorithm GB/s on 1 MI355X" if op == "allreduce"
+                  else f"ring {op.replace('_', '-')} algorithm GB/s on 1 MI355X",
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": cfg["name"], "W": W, "count_per_rank": count, "bytes_per_rank": S,
-                   "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": bool(args.fuse_rs_ag),
+        "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
+                   "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
                    "inplace": bool(args.inplace), "launches_per_step": launches},
         "algbw_rank_equiv_GBps": round(W * value, 2),
         "call_hbm_GBps": round(call_bytes / (ms_per_step * 1e-3) / 1e9, 1),

@@ -94,10 +94,12 @@ typedef struct hcl_opts {
   size_t workspace_bytes;
   void *host_stage;        /* pinned host inboxes; see hcl_host_stage_bytes                 */
   size_t host_stage_bytes;
-  int threads;             /* threads per workgroup: 0 = default, else 64..1024, multiple of 64 */
+  int threads;             /* threads per workgroup: 0 = default (128 stepwise, 64 fused), else
+                              64..1024, multiple of 64                                        */
   int blocks;              /* workgroups per launch: 0 = default (one tile per workgroup); smaller
                               values give a persistent grid striding over the tiles            */
-  int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default, 1, 2, 4 or 8 */
+  int unroll;              /* 128-bit vectors in flight per thread and source (step kernels):
+                              0 = default (4), else 1, 2, 4 or 8                              */
   int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the

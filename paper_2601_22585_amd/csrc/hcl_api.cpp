@@ -236,7 +236,9 @@ struct Ctx {
     int unroll = o && o->unroll ? o->unroll : env_int("HCL_UNROLL", 0);
     int blocks = o && o->blocks ? o->blocks : env_int("HCL_BLOCKS", 0);
     int nt = o && o->nontemporal ? o->nontemporal : env_int("HCL_NONTEMPORAL", 0);
-    if (threads == 0) threads = 256;
+    // defaults from sweeps on MI355X: 8 KiB per source and workgroup for the step
+    // kernels, single-wavefront workgroups for the fused kernels
+    if (threads == 0) threads = sched == HCL_SCHED_FUSED ? 64 : 128;
     if (unroll == 0) unroll = 4;
     if (threads < 64 || threads > 1024 || threads % 64) return fail(HCL_ERR_INVALID_ARG, "threads = %d must be a multiple of 64 in [64,1024]", threads);
     if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return fail(HCL_ERR_INVALID_ARG, "unroll = %d must be 1, 2, 4 or 8", unroll);

@@ -43,13 +43,19 @@ __device__ __forceinline__ void st16(char* p, u32x4 v) {
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 
-// binary32 -> bfloat16, round to nearest even, result in the top 16 bits
-// (low 16 bits zero).  NaN keeps its sign and gets the quiet bit.
-__device__ __forceinline__ uint32_t bf16_round_hi(float s) {
-  const uint32_t u = f2u(s);
-  const uint32_t rounded = u + 0x7FFFu + ((u >> 16) & 1u);
-  const bool is_nan = (u & 0x7FFFFFFFu) > 0x7F800000u;
-  return (is_nan ? (u | 0x00400000u) : rounded) & 0xFFFF0000u;
+// binary32 pair -> packed bfloat16 pair with the gfx950 conversion instruction
+// (v_cvt_pk_bf16_f32): round to nearest even, subnormal results kept, NaN stays
+// NaN.  lo lands in bits 0..15, hi in bits 16..31.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
+  f32x2 s;
+  s.x = lo;
+  s.y = hi;
+  const bf16x2 r = __builtin_convertvector(s, bf16x2);
+  uint32_t u;
+  __builtin_memcpy(&u, &r, 4);
+  return u;
 }
 
 template <int DT> struct Wire;
@@ -69,11 +75,11 @@ template <> struct Wire<DT_BF16> {
   __device__ static __forceinline__ uint32_t hop_word(uint32_t in, uint32_t loc) {
     const float lo = u2f(in << 16) + u2f(loc << 16);
     const float hi = u2f(in & 0xFFFF0000u) + u2f(loc & 0xFFFF0000u);
-    return (bf16_round_hi(lo) >> 16) | bf16_round_hi(hi);
+    return bf16_pack_rne(lo, hi);
   }
   __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) {
     const float s = u2f((uint32_t)in << 16) + u2f((uint32_t)loc << 16);
-    return (elem_t)(bf16_round_hi(s) >> 16);
+    return (elem_t)(bf16_pack_rne(s, 0.0f) & 0xFFFFu);
   }
 };
 template <> struct Wire<DT_FP16> {

@@ -213,3 +213,20 @@ def test_runs_on_a_side_stream_and_under_graph_capture():
         torch.cuda.synchronize()
         for r in range(W):
             assert_same_bits(recv[r], want[r], dtype, f"graph replay {rep} rank {r}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_single_hop_over_all_bit_patterns(dtype):
+    """W = 2 makes every output one hop: all 2^16 patterns of one operand against a
+    set of partners chosen to hit ties, subnormal results, overflow, zeros, inf and NaN."""
+    allp = torch.arange(0, 1 << 16, dtype=torch.int32).to(torch.int16)
+    inf = 0x7F80 if dtype == "bf16" else 0x7C00
+    partners = [0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x03FF, 0x0400, inf, inf | 0x8000, inf + 1,
+                inf - 1, (inf - 1) | 0x8000, 0x3F80, 0xBF80, 0x3C00, 0xBC00, 0x3F81, 0x3C01, 0x0002, 0x8002]
+    g = torch.Generator().manual_seed(3)
+    partners += torch.randint(0, 1 << 16, (43,), generator=g).tolist()
+    a = allp.repeat(len(partners)).view(wl.TORCH_DTYPE[dtype])
+    b = torch.tensor(partners, dtype=torch.int32).to(torch.int16).repeat_interleave(1 << 16).view(wl.TORCH_DTYPE[dtype])
+    for sched in ("stepwise", "fused"):
+        run_allreduce(0, 2, a.numel(), dtype, None, cpu_inputs=[a, b], sched=sched)
+        run_allreduce(0, 2, a.numel(), dtype, None, cpu_inputs=[b, a], sched=sched, misalign=1)
