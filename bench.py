@@ -87,6 +87,8 @@ def parse():
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=0)
     ap.add_argument("--chunk-bytes", type=int, default=-1)
+    ap.add_argument("--skew-bytes", type=int, default=0,
+                    help="start the k-th allocated buffer k * skew bytes into its allocation (layout experiments)")
     return ap.parse_args()
 
 
@@ -136,8 +138,12 @@ def main():
         name = f"{name}:{op}"
 
     # ---- buffers: seeded inputs generated on the device ----
+    nalloc = [0]
+
     def new(n):
-        return torch.empty(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda")
+        pad = (nalloc[0] * args.skew_bytes) // es
+        nalloc[0] += 1
+        return torch.empty(n + pad, dtype=wl.TORCH_DTYPE[dtype], device="cuda")[pad:]
 
     opt = dict(sched=args.sched, xport=xport, threads=args.threads, blocks=args.blocks, unroll=args.unroll,
                nontemporal=args.nontemporal)

@@ -39,6 +39,14 @@
  *   - Base pointers must be aligned to the element size.  The 128-bit fast
  *     path needs 16-byte aligned base pointers, block offsets and chunk sizes;
  *     anything else runs on a slower element-wise path with the same result.
+ *   - Layout advice: rank buffers whose addresses are all congruent modulo a
+ *     large power of two (say, every buffer 2 GiB-aligned) make the streams of
+ *     a step fall into the same DRAM banks; starting successive buffers
+ *     64 KiB + 256 B further into their allocations was worth up to 7 % on
+ *     MI355X.  The library skews its own workspace and inbox slots that way.
+ *   - Launch-shape fields of hcl_opts_t that are 0 may be overridden by the
+ *     environment variables HCL_THREADS, HCL_UNROLL, HCL_BLOCKS and
+ *     HCL_NONTEMPORAL (for sweeps); values in the struct win.
  *   - Calls are re-entrant; the only global state is cached device properties
  *     and the thread-local error string.
  */
@@ -99,7 +107,7 @@ typedef struct hcl_opts {
   int blocks;              /* workgroups per launch: 0 = default (one tile per workgroup); smaller
                               values give a persistent grid striding over the tiles            */
   int unroll;              /* 128-bit vectors in flight per thread and source (step kernels):
-                              0 = default (4), else 1, 2, 4 or 8                              */
+                              0 = default (2), else 1, 2, 4 or 8                              */
   int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the
@@ -169,13 +177,14 @@ hcl_status_t hcl_all_gather_sim(const void *const *send, void *const *recv, int 
 /* Device scratch the call of this kind and shape needs in opts->workspace
  * (0 for everything except an out-of-place STEPWISE Reduce-Scatter with W > 2,
  * where the caller cannot say "in place" here: the figure is the out-of-place
- * one).  `count` is the per-call count argument of that entry point.  Returns
+ * one: 2 * W slots of one block rounded up to 256 bytes plus a 64 KiB + 256 B
+ * skew).  `count` is the per-call count argument of that entry point.  Returns
  * 0 on invalid arguments too. */
 size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                            const hcl_opts_t *opts);
 
 /* Pinned host memory the HOST_STAGED transport needs in opts->host_stage:
- * two inbox slots of one block per rank.  0 for the DIRECT transport. */
+ * two inbox slots (sized like the workspace slots) of one block per rank.  0 for the DIRECT transport. */
 size_t hcl_host_stage_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                             const hcl_opts_t *opts);
 

@@ -106,17 +106,19 @@ def test_staging_and_workspace_rules():
 
 
 def test_workspace_and_host_stage_sizes():
-    # out-of-place stepwise reduce-scatter: two slots of one block per rank, 256-byte granules
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * 2 * (1 << 21)
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * 2 * 512
+    # out-of-place stepwise reduce-scatter: two slots per rank, each one block rounded up to
+    # 256 bytes plus the 64 KiB + 256 B skew between slots
+    skew = 65536 + 256
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * 2 * ((1 << 21) + skew)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * 2 * (512 + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 2, 1 << 20, hcl.BF16) == 0
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16, sched="fused") == 0
     assert hcl.workspace_bytes(hcl.KIND_ALLREDUCE, 8, 1 << 20, hcl.BF16) == 0
     assert hcl.workspace_bytes(hcl.KIND_ALL_GATHER, 8, 1 << 20, hcl.BF16) == 0
     # staged: two inbox slots of one block per rank; All-Reduce blocks are ceil(count / W)
-    assert hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, 8, 134217728, hcl.FP32, xport="host_staged") == 8 * 2 * (64 << 20)
+    assert hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, 8, 134217728, hcl.FP32, xport="host_staged") == 8 * 2 * ((64 << 20) + skew)
     assert hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, 8, 134217728, hcl.FP32) == 0
-    assert hcl.host_stage_bytes(hcl.KIND_REDUCE_SCATTER, 4, 1000, hcl.FP16, xport="host_staged") == 4 * 2 * 2048
+    assert hcl.host_stage_bytes(hcl.KIND_REDUCE_SCATTER, 4, 1000, hcl.FP16, xport="host_staged") == 4 * 2 * (2048 + skew)
 
 
 @pytest.mark.parametrize("W", list(range(1, 17)))
