@@ -87,6 +87,8 @@ def parse():
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=0)
     ap.add_argument("--chunk-bytes", type=int, default=-1)
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one call into a HIP graph and time K replays (latency regime; no events)")
     ap.add_argument("--skew-bytes", type=int, default=0,
                     help="start the k-th allocated buffer k * skew bytes into its allocation (layout experiments)")
     return ap.parse_args()
@@ -249,18 +251,30 @@ def main():
     phase_mode = not args.per_launch_events
     n_phases = 2 if (op == "allreduce" and args.sched == "stepwise" and W > 1) else 1
     per = (n_phases if phase_mode else launches) + 1
-    ev = None if (args.no_events or launches == 0) else hcl.EventList(K * per)
+    ev = None if (args.no_events or args.graph or launches == 0) else hcl.EventList(K * per)
     stream = torch.cuda.current_stream()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(K):
-        o = dict(opt)
-        if ev is not None:
-            o["events"] = (ev, k * per, per)
-            o["events_per_phase"] = phase_mode
-        call(send, recv, chunk_bytes=chunk_bytes, stream=stream, **o)
-    torch.cuda.synchronize()
-    t_total = time.perf_counter() - t0
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call(send, recv, chunk_bytes=chunk_bytes, **opt)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_total = time.perf_counter() - t0
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            o = dict(opt)
+            if ev is not None:
+                o["events"] = (ev, k * per, per)
+                o["events_per_phase"] = phase_mode
+            call(send, recv, chunk_bytes=chunk_bytes, stream=stream, **o)
+        torch.cuda.synchronize()
+        t_total = time.perf_counter() - t0
     ms_per_step = t_total / K * 1e3
 
     # ---- algorithmic bytes: of the whole call, and of one launch of the dominant kernel ----
@@ -310,10 +324,15 @@ def main():
                 "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_ms, 5), "launches_timed": timed,
                 "timing": how}
         if staged:
-            # every block that travels is written to host memory once and read back once
+            # every block that travels is written to host memory once and read back once; the host
+            # link bounds this path (PCIe Gen5 x16: 64 GB/s nominal each way), not HBM
             link = (2 * (W - 1) if op == "allreduce" else (W - 1)) * S
-            roof["note"] = "staged transport: the host link, not HBM, bounds this path"
-            roof["link_GBps_each_way"] = round(link / (ms_per_step * 1e-3) / 1e9, 2)
+            link_gbps = link / (ms_per_step * 1e-3) / 1e9
+            roof = {"bound": "pcie", "kernel": "reduce_copy_vec with pinned-host operands", "achieved": round(link_gbps, 2),
+                    "peak": 64.0, "unit": "GB/s", "frac": round(link_gbps / 64.0, 4), "traffic": None,
+                    "bytes_each_way_per_step": int(link),
+                    "timing": "whole step; every transfer crosses the link once in each direction",
+                    "hbm_kernel": roof}
         ev.close()
 
     value = S / (ms_per_step * 1e-3) / 1e9
@@ -325,7 +344,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
                    "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
-                   "inplace": bool(args.inplace), "launches_per_step": launches},
+                   "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph)},
         "algbw_rank_equiv_GBps": round(W * value, 2),
         "call_hbm_GBps": round(call_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "call_hbm_frac_of_peak": round(call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

@@ -40,6 +40,10 @@
  *   - A chunk is a contiguous run of chunk_elems elements inside a block.  It
  *     only orders the element loop; it never changes a value.
  *
+ *   - Reduce / Broadcast travel along the same ring as chains that end
+ *     (Reduce) or start (Broadcast) at the root; Reduce therefore sums in the
+ *     order next(root), ..., root.  All-to-All is the plain block transpose.
+ *
  * Pins (tests/, marker "not gpu"): exact-rational brute force of the closed
  * form fold on tiny inputs; the hand-derived cancellation example under
  * tests/golden/; W = 2 against numpy / torch elementwise adds; integer-valued
@@ -327,6 +331,75 @@ int orc_all_gather(const void *const *in, void *const *out, int W, size_t sendco
         memcpy((unsigned char *)out[r] + (size_t)r * sendcount * es, in[r], sendcount * es);
     return ring_phase(out, W, (size_t)W * sendcount, sendcount, dtype, ring,
                       chunk_elems, ORC_PHASE_AG);
+}
+
+/* ------------------------------------------------------------------ */
+/* the other collectives the paper evaluates (Appendix E.1 "Other       */
+/* Collective Communication Operations"): Reduce, Broadcast, All-to-All */
+/* ------------------------------------------------------------------ */
+
+/* Reduce (sum) to `root` along the ring, as a chain of messages: the rank
+   after the root sends its vector to its successor, every following rank adds
+   its own vector to what arrived (incoming operand on the left, one hop per
+   rank, rounded to the wire type) and passes the partial on; the chain ends at
+   the root.  in[r]: count elements, untouched.  out: count elements, the
+   root's result.  The fold order equals that of block `root` of the ring
+   All-Reduce, applied to the whole vector. */
+int orc_reduce(const void *const *in, void *out, int W, size_t count, int dtype,
+               const int *ring, int root, size_t chunk_elems)
+{
+    int pos[64];
+    if (!args_ok(W, dtype) || root < 0 || root >= W) return ORC_BAD_ARG;
+    if (!ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype), C = chunk_elems ? chunk_elems : count, c0;
+    unsigned char *msg = (unsigned char *)malloc(count * es + 1);
+    unsigned char *mine = (unsigned char *)malloc(count * es + 1);
+    if (!msg || !mine) { free(msg); free(mine); return ORC_NO_MEM; }
+    /* first sender: the rank after the root */
+    memcpy(msg, in[ring_at(ring, wrap(pos[root] + 1, W))], count * es);
+    for (int k = 2; k <= W; ++k) {
+        int r = ring_at(ring, wrap(pos[root] + k, W));      /* receives msg, adds its own */
+        memcpy(mine, in[r], count * es);
+        for (c0 = 0; c0 < count; c0 += C) {
+            size_t n = (count - c0 < C) ? count - c0 : C;
+            hop_run(mine + c0 * es, msg + c0 * es, n, dtype);
+        }
+        memcpy(msg, mine, count * es);                      /* the partial travels on */
+    }
+    memcpy(out, msg, count * es);                           /* W == 1: the root's own vector */
+    free(msg); free(mine);
+    return ORC_OK;
+}
+
+/* Broadcast from `root` along the ring: out[r] (count elements) becomes a copy
+   of `in` for every rank, each rank copying what its predecessor holds. */
+int orc_broadcast(const void *in, void *const *out, int W, size_t count, int dtype,
+                  const int *ring, int root)
+{
+    int pos[64];
+    if (!args_ok(W, dtype) || root < 0 || root >= W) return ORC_BAD_ARG;
+    if (!ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype);
+    memcpy(out[root], in, count * es);
+    for (int k = 1; k < W; ++k) {
+        int r = ring_at(ring, wrap(pos[root] + k, W));
+        int p = ring_at(ring, wrap(pos[root] + k - 1, W));
+        memcpy(out[r], out[p], count * es);
+    }
+    return ORC_OK;
+}
+
+/* All-to-All: in[r] and out[r] hold W blocks of n elements; block q of out[r]
+   is block r of in[q].  (The plain definition; no ring is involved.) */
+int orc_alltoall(const void *const *in, void *const *out, int W, size_t n, int dtype)
+{
+    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype);
+    for (int r = 0; r < W; ++r)
+        for (int q = 0; q < W; ++q)
+            memcpy((unsigned char *)out[r] + (size_t)q * n * es,
+                   (const unsigned char *)in[q] + (size_t)r * n * es, n * es);
+    return ORC_OK;
 }
 
 /* bulk conversions, for the conversion pins */

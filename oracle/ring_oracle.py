@@ -49,6 +49,9 @@ def lib():
             getattr(L, name).restype = None
         L.orc_hop_n.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
         L.orc_hop_n.restype = None
+        L.orc_reduce.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int, ctypes.c_size_t]
+        L.orc_broadcast.argtypes = [ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int]
+        L.orc_alltoall.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int]
         L.orc_set_threads.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
@@ -135,6 +138,36 @@ def all_gather(inputs, dtype, ring=None, chunk_elems=0):
     out = [np.zeros(W * n, dtype=NP_WIRE[dtype]) for _ in range(W)]
     _check(lib().orc_all_gather(_ptrs(src), _ptrs(out), W, n, dtype, _ring_arg(ring, W), chunk_elems),
            "all_gather")
+    return out
+
+
+def reduce(inputs, dtype, root, ring=None, chunk_elems=0):
+    """Ring Reduce (sum) to `root`.  inputs: W arrays of count elements.  Returns the root's result."""
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    n = src[0].size
+    assert all(s.size == n for s in src)
+    out = np.zeros(n, dtype=NP_WIRE[dtype])
+    _check(lib().orc_reduce(_ptrs(src), out.ctypes.data, W, n, dtype, _ring_arg(ring, W), root, chunk_elems), "reduce")
+    return out
+
+
+def broadcast(root_input, dtype, W, root, ring=None):
+    """Ring Broadcast from `root`.  Returns W arrays, each a copy of root_input."""
+    src = _wire(root_input, dtype)
+    out = [np.zeros(src.size, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_broadcast(src.ctypes.data, _ptrs(out), W, src.size, dtype, _ring_arg(ring, W), root), "broadcast")
+    return out
+
+
+def alltoall(inputs, dtype):
+    """All-to-All.  inputs: W arrays of W*n elements.  Returns W arrays of W*n elements."""
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    total = src[0].size
+    assert total % W == 0 and all(s.size == total for s in src)
+    out = [np.zeros(total, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_alltoall(_ptrs(src), _ptrs(out), W, total // W, dtype), "alltoall")
     return out
 
 

@@ -137,3 +137,17 @@ def allreduce(inputs, fmt, ring=None):
                 acc = hop_int32(acc, inputs[r][i]) if fmt == "int32" else hop(acc, inputs[r][i], fmt)
             out[i] = acc
     return out
+
+
+def reduce(inputs, fmt, root, ring=None):
+    """Ring Reduce to `root`: every element summed in the order next(root), ..., root."""
+    W = len(inputs)
+    ring = list(range(W)) if ring is None else list(ring)
+    order = fold_order(root, ring)
+    out = []
+    for i in range(len(inputs[0])):
+        acc = inputs[order[0]][i]
+        for r in order[1:]:
+            acc = hop_int32(acc, inputs[r][i]) if fmt == "int32" else hop(acc, inputs[r][i], fmt)
+        out.append(acc)
+    return out
