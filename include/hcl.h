@@ -90,7 +90,10 @@ typedef enum { HCL_SCHED_STEPWISE = 0, HCL_SCHED_FUSED = 1 } hcl_sched_t;
  *   RDMA"; Appendix F.1), local operands and results stay in device memory. */
 typedef enum { HCL_XPORT_DIRECT = 0, HCL_XPORT_HOST_STAGED = 1 } hcl_xport_t;
 
-typedef enum { HCL_KIND_ALLREDUCE = 0, HCL_KIND_REDUCE_SCATTER = 1, HCL_KIND_ALL_GATHER = 2 } hcl_kind_t;
+typedef enum {
+  HCL_KIND_ALLREDUCE = 0, HCL_KIND_REDUCE_SCATTER = 1, HCL_KIND_ALL_GATHER = 2,
+  HCL_KIND_REDUCE = 3, HCL_KIND_BROADCAST = 4, HCL_KIND_ALLTOALL = 5
+} hcl_kind_t;
 typedef enum { HCL_PHASE_RS = 0, HCL_PHASE_AG = 1 } hcl_phase_t;
 
 /* Optional settings; a NULL hcl_opts_t* or a zero-filled struct means defaults. */
@@ -174,8 +177,48 @@ hcl_status_t hcl_all_gather_sim(const void *const *send, void *const *recv, int 
                                 hcl_dtype_t dtype, size_t chunk_bytes,
                                 const hcl_opts_t *opts, void *stream);
 
+/*
+ * Reduce (sum) to `root` along the ring -- one of the further collectives the
+ * paper evaluates (Appendix E.1 "Other Collective Communication Operations").
+ * send[r] holds `count` elements for every rank; only recv[root] is written
+ * (the other recv entries are ignored and may be NULL).  The rank after the
+ * root sends its vector on, every following rank adds its own with one hop, the
+ * chain ends at the root: the sum runs in the order next(root), ..., root, i.e.
+ * as block `root` of the All-Reduce does.  In place: recv[root] == send[root].
+ * STEPWISE (W - 1 launches) with W > 2 keeps the travelling partial in
+ * opts->workspace (hcl_workspace_bytes with HCL_KIND_REDUCE: two slots of the
+ * vector); FUSED is one launch and needs none.  DIRECT transport only.
+ */
+hcl_status_t hcl_reduce_sim(const void *const *send, void *const *recv, int W, size_t count,
+                            hcl_dtype_t dtype, hcl_op_t op, int root, size_t chunk_bytes,
+                            const hcl_opts_t *opts, void *stream);
+
+/*
+ * Broadcast from `root` along the ring (same passage).  Only send[root] is read
+ * (`count` elements; other send entries are ignored and may be NULL); every
+ * recv[r] receives a copy, each rank copying what its predecessor holds
+ * (STEPWISE, W - 1 launches) or all at once from the root (FUSED, one launch).
+ * In place: recv[root] == send[root].  DIRECT transport only.
+ */
+hcl_status_t hcl_broadcast_sim(const void *const *send, void *const *recv, int W, size_t count,
+                               hcl_dtype_t dtype, int root, size_t chunk_bytes,
+                               const hcl_opts_t *opts, void *stream);
+
+/*
+ * All-to-All (same passage; the expert-parallel exchange of Appendix B.1).
+ * send[r] and recv[r] hold W blocks of `count` elements; block q of recv[r]
+ * becomes block r of send[q].  No in-place form: any overlap is HCL_ERR_ALIAS.
+ * STEPWISE: W launches, launch k moving the blocks every rank receives from the
+ * rank k places before it in the ring; FUSED: the same copies packed into as few
+ * launches as the per-launch segment table (32 entries) allows.  DIRECT only.
+ */
+hcl_status_t hcl_alltoall_sim(const void *const *send, void *const *recv, int W, size_t count,
+                              hcl_dtype_t dtype, size_t chunk_bytes,
+                              const hcl_opts_t *opts, void *stream);
+
 /* Device scratch the call of this kind and shape needs in opts->workspace
- * (0 for everything except an out-of-place STEPWISE Reduce-Scatter with W > 2,
+ * (0 for everything except a STEPWISE Reduce with W > 2 -- two slots of the
+ * vector -- and an out-of-place STEPWISE Reduce-Scatter with W > 2,
  * where the caller cannot say "in place" here: the figure is the out-of-place
  * one: 2 * W slots of one block rounded up to 256 bytes plus a 64 KiB + 256 B
  * skew).  `count` is the per-call count argument of that entry point.  Returns

@@ -309,7 +309,9 @@ struct Ctx {
 
   hcl_status_t launch(FusedArgs& a) {
     if (a.count == 0) return HCL_OK;
-    bool al = (a.B * es) % 16 == 0;
+    const bool one_block = a.mode >= 3;  // Reduce / Broadcast
+    const bool copy_mode = a.mode == 2 || a.mode == 4;
+    bool al = one_block || (a.B * es) % 16 == 0;
     for (int r = 0; r < W; ++r)
       if (((uintptr_t)a.src[r] | (uintptr_t)a.dst[r]) & 15) al = false;
     uint64_t chunk = (chunk_elems && chunk_elems < a.B) ? chunk_elems : a.B;
@@ -317,10 +319,10 @@ struct Ctx {
     if (nchunks > 1 && (chunk * es) % 16) al = false;
     Tuning t = tune;
     t.vec = al;
-    t.unroll = a.mode == 2 ? 4 : fused_unroll(W);
+    t.unroll = copy_mode ? 4 : fused_unroll(W);
     const uint64_t tile = tile_elems(dtype, t);
     const uint64_t tpc = ceil_div(chunk, tile);
-    const uint64_t total = nchunks * (uint64_t)W * tpc;
+    const uint64_t total = nchunks * (uint64_t)(one_block ? 1 : W) * tpc;
     if (total > 0x7FFFFFFFull) return fail(HCL_ERR_INVALID_ARG, "collective needs %llu tiles, more than one launch can index", (unsigned long long)total);
     a.chunk = chunk;
     a.tiles_per_chunk = (uint32_t)tpc;
@@ -429,8 +431,10 @@ extern "C" size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t
   (void)chunk_bytes;
   if (W < 1 || W > kMaxRanks || !dtype_ok(dtype)) return 0;
   const int sched = opts ? opts->sched : 0, xport = opts ? opts->xport : 0;
-  if (kind != HCL_KIND_REDUCE_SCATTER || sched != HCL_SCHED_STEPWISE || xport != HCL_XPORT_DIRECT || W <= 2) return 0;
+  if (sched != HCL_SCHED_STEPWISE || xport != HCL_XPORT_DIRECT || W <= 2) return 0;
   if (size_overflows(count, 2 * (uint64_t)W, elem_size(dtype))) return 0;
+  if (kind == HCL_KIND_REDUCE) return (size_t)(slot_bytes_for(count, elem_size(dtype)) * 2);
+  if (kind != HCL_KIND_REDUCE_SCATTER) return 0;
   return (size_t)(slot_bytes_for(count, elem_size(dtype)) * 2 * W);
 }
 
@@ -551,11 +555,12 @@ static hcl_status_t run_ag(Ctx& c, const BlockMap& bm, char* const* buf, const v
 }
 
 static void fill_fused(const Ctx& c, FusedArgs& f, const void* const* send, void* const* recv,
-                       uint64_t count, uint64_t B, int mode) {
+                       uint64_t count, uint64_t B, int mode, int root = 0) {
   memset(&f, 0, sizeof f);
+  f.root = (uint32_t)root;
   for (int r = 0; r < c.W; ++r) {
-    f.src[r] = (const char*)send[r];
-    f.dst[r] = (char*)recv[r];
+    f.src[r] = send ? (const char*)send[r] : nullptr;
+    f.dst[r] = recv ? (char*)recv[r] : nullptr;
     f.order[r] = (uint8_t)c.ring.order[r];
     f.pos[r] = (uint8_t)c.ring.pos[r];
   }
@@ -727,6 +732,159 @@ extern "C" hcl_status_t hcl_all_gather_sim(const void* const* send, void* const*
   }
   if (W > 1) {
     if ((st = run_ag(c, bm, buf, (inplace || staged) ? nullptr : send, 0, ib, 0))) return st;
+  }
+  return c.finish();
+}
+
+
+// ---------------------------------------------------------------------------
+// Reduce, Broadcast, All-to-All: the other collectives the paper evaluates
+// (Appendix E.1 "Other Collective Communication Operations"), on the same kernels
+// ---------------------------------------------------------------------------
+static hcl_status_t only_direct(const Ctx& c, const char* what) {
+  if (c.xport != HCL_XPORT_DIRECT) return fail(HCL_ERR_UNSUPPORTED, "%s has no staged transport", what);
+  return HCL_OK;
+}
+
+extern "C" hcl_status_t hcl_reduce_sim(const void* const* send, void* const* recv, int W, size_t count,
+                                       hcl_dtype_t dtype, hcl_op_t op, int root, size_t chunk_bytes,
+                                       const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
+  if ((st = only_direct(c, "Reduce"))) return st;
+  if (root < 0 || root >= W) return fail(HCL_ERR_INVALID_ARG, "root %d out of range", root);
+  if (size_overflows(count, 1, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (count == 0) return c.finish();
+  if (!send || !recv || !recv[root]) return fail(HCL_ERR_INVALID_ARG, "null send array or null recv[root]");
+  for (int r = 0; r < W; ++r) {
+    if (!send[r]) return fail(HCL_ERR_INVALID_ARG, "null send buffer for rank %d", r);
+    if ((uintptr_t)send[r] % c.es) return fail(HCL_ERR_INVALID_ARG, "send buffer of rank %d is not aligned to the element size", r);
+  }
+  if ((uintptr_t)recv[root] % c.es) return fail(HCL_ERR_INVALID_ARG, "recv[root] is not aligned to the element size");
+  const uint64_t es = c.es, bytes = count * es;
+  char* ws = nullptr;
+  uint64_t slot = 0, need = 0;
+  if (c.sched == HCL_SCHED_STEPWISE && W > 2) {
+    slot = slot_bytes_for(count, es);
+    need = 2 * slot;
+    if (!opts || !opts->workspace) return fail(HCL_ERR_WORKSPACE, "stepwise Reduce needs opts->workspace (%llu bytes)", (unsigned long long)need);
+    if (opts->workspace_bytes < need) return fail(HCL_ERR_WORKSPACE, "workspace has %zu bytes, %llu needed", opts->workspace_bytes, (unsigned long long)need);
+    if ((uintptr_t)opts->workspace % 16) return fail(HCL_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    ws = (char*)opts->workspace;
+  }
+  const Range out{(const char*)recv[root], bytes}, wsr{ws, need};
+  for (int r = 0; r < W; ++r) {
+    const Range in{(const char*)send[r], bytes};
+    if (!(r == root && send[r] == recv[root]) && out.overlaps(in)) return fail(HCL_ERR_ALIAS, "recv[root] overlaps the send buffer of rank %d", r);
+    if (wsr.overlaps(in)) return fail(HCL_ERR_ALIAS, "workspace overlaps the send buffer of rank %d", r);
+  }
+  if (wsr.overlaps(out)) return fail(HCL_ERR_ALIAS, "workspace overlaps recv[root]");
+
+  if ((st = c.phase())) return st;
+  if (W == 1) {
+    StepArgs a{};
+    if (send[0] != recv[0]) add_seg(a, send[0], nullptr, recv[0], nullptr, count);
+    if ((st = c.launch(a, 1, 1))) return st;
+    return c.finish();
+  }
+  if (c.sched == HCL_SCHED_FUSED) {
+    FusedArgs f;
+    fill_fused(c, f, send, recv, count, count, 3, root);
+    for (int r = 0; r < W; ++r)
+      if (r != root) f.dst[r] = nullptr;
+    if ((st = c.launch(f))) return st;
+    return c.finish();
+  }
+  // hop k (1 .. W-1): the k-th rank after the first sender adds its vector to what arrived
+  const int p0 = c.ring.pos[root];
+  for (int k = 1; k <= W - 1; ++k) {
+    const int r = c.ring.at(p0 + 1 + k), p = c.ring.at(p0 + k);
+    const char* in = k == 1 ? (const char*)send[p] : ws + ((k - 1) & 1) * slot;
+    char* out_p = k == W - 1 ? (char*)recv[root] : ws + (k & 1) * slot;
+    StepArgs a{};
+    add_seg(a, in, send[r], out_p, nullptr, count);
+    if ((st = c.launch(a, 2, 1))) return st;
+  }
+  return c.finish();
+}
+
+extern "C" hcl_status_t hcl_broadcast_sim(const void* const* send, void* const* recv, int W, size_t count,
+                                          hcl_dtype_t dtype, int root, size_t chunk_bytes,
+                                          const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if ((st = only_direct(c, "Broadcast"))) return st;
+  if (root < 0 || root >= W) return fail(HCL_ERR_INVALID_ARG, "root %d out of range", root);
+  if (size_overflows(count, 1, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (count == 0) return c.finish();
+  if (!send || !recv || !send[root]) return fail(HCL_ERR_INVALID_ARG, "null recv array or null send[root]");
+  if ((uintptr_t)send[root] % c.es) return fail(HCL_ERR_INVALID_ARG, "send[root] is not aligned to the element size");
+  const uint64_t bytes = count * c.es;
+  const Range in{(const char*)send[root], bytes};
+  for (int r = 0; r < W; ++r) {
+    if (!recv[r]) return fail(HCL_ERR_INVALID_ARG, "null recv buffer for rank %d", r);
+    if ((uintptr_t)recv[r] % c.es) return fail(HCL_ERR_INVALID_ARG, "recv buffer of rank %d is not aligned to the element size", r);
+    const Range o{(const char*)recv[r], bytes};
+    if (!(r == root && recv[r] == send[root]) && o.overlaps(in)) return fail(HCL_ERR_ALIAS, "recv buffer of rank %d overlaps send[root]", r);
+    for (int q = 0; q < r; ++q)
+      if (o.overlaps(Range{(const char*)recv[q], bytes})) return fail(HCL_ERR_ALIAS, "recv buffers of ranks %d and %d overlap", q, r);
+  }
+  if ((st = c.phase())) return st;
+  if (c.sched == HCL_SCHED_FUSED) {
+    FusedArgs f;
+    fill_fused(c, f, nullptr, recv, count, count, 4, root);
+    f.src[root] = (const char*)send[root];
+    if ((st = c.launch(f))) return st;
+    return c.finish();
+  }
+  // hop k: the k-th rank after the root copies what its predecessor holds; the
+  // first launch also puts the root's vector into its own result when out of place
+  const int p0 = c.ring.pos[root];
+  bool own_done = send[root] == recv[root];
+  for (int k = 1; k <= W - 1 || !own_done; ++k) {
+    StepArgs a{};
+    if (!own_done) {
+      add_seg(a, send[root], nullptr, recv[root], nullptr, count);
+      own_done = true;
+    }
+    if (k <= W - 1) {
+      const int r = c.ring.at(p0 + k), p = c.ring.at(p0 + k - 1);
+      add_seg(a, k == 1 ? send[root] : (const void*)recv[p], nullptr, recv[r], nullptr, count);
+    }
+    if ((st = c.launch(a, 1, 1))) return st;
+  }
+  return c.finish();
+}
+
+extern "C" hcl_status_t hcl_alltoall_sim(const void* const* send, void* const* recv, int W, size_t count,
+                                         hcl_dtype_t dtype, size_t chunk_bytes,
+                                         const hcl_opts_t* opts, void* stream) {
+  Ctx c;
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  if (st) return st;
+  if ((st = only_direct(c, "All-to-All"))) return st;
+  if (size_overflows(count, (uint64_t)W, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
+  if (count == 0) return c.finish();
+  if ((st = check_ptrs(send, recv, W, c.es))) return st;
+  const uint64_t n = count, es = c.es, bytes = n * W * es;
+  if ((st = check_alias(send, recv, W, bytes, bytes, nullptr, 0, /*inplace=*/false, false))) return st;
+  if ((st = c.phase())) return st;
+  // exchange k: every rank receives the block addressed to it from the rank k places
+  // before it in the ring (k = 0: its own block).  STEPWISE: one launch per exchange;
+  // FUSED: as many exchanges per launch as the launch's segment table holds.
+  const int per_launch = c.sched == HCL_SCHED_FUSED ? kMaxSegs / W : 1;
+  for (int k0 = 0; k0 < W; k0 += per_launch) {
+    StepArgs a{};
+    for (int k = k0; k < k0 + per_launch && k < W; ++k) {
+      for (int i = 0; i < W; ++i) {
+        const int r = c.ring.order[i], q = c.ring.at(i - k);
+        add_seg(a, off(send[q], (uint64_t)r * n, es), nullptr, off(recv[r], (uint64_t)q * n, es), nullptr, n);
+      }
+    }
+    if ((st = c.launch(a, 1, 1))) return st;
   }
   return c.finish();
 }

@@ -30,8 +30,8 @@ struct StepArgs {
 
 // Whole-collective launch: every element's ring pass stays in one thread.
 struct FusedArgs {
-  const char* src[16];  // per rank, start of its full vector (AR, RS) or of its shard (AG)
-  char* dst[16];        // per rank, start of its full vector (AR, AG) or of its shard (RS)
+  const char* src[16];  // per rank, start of its full vector (AR, RS, Reduce) or of its shard (AG)
+  char* dst[16];        // per rank, start of its full vector (AR, AG, Broadcast) or of its shard (RS)
   uint8_t order[16];    // ring order
   uint8_t pos[16];      // ring position of each rank
   uint64_t count;       // elements in the full vector
@@ -40,7 +40,9 @@ struct FusedArgs {
   uint32_t tiles_per_chunk;
   uint32_t total_tiles;
   uint32_t W;
-  uint32_t mode;        // 0 All-Reduce, 1 Reduce-Scatter, 2 All-Gather
+  uint32_t mode;        // 0 All-Reduce, 1 Reduce-Scatter, 2 All-Gather, 3 Reduce, 4 Broadcast
+  uint32_t root;        // Reduce / Broadcast: the whole vector is one block that belongs to this rank
+  uint32_t pad_;
 };
 
 struct Tuning {

@@ -245,11 +245,12 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * U;
   const bool to_all = a.mode == 0;
+  const bool whole = a.mode == 3;  // Reduce: one block, the whole vector, summed in the root's order
 
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, W, a.chunk, tile);
-    const uint32_t c = p.d;
-    uint64_t blo = (uint64_t)c * a.B, bhi = blo + a.B;
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : (uint32_t)W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
     if (blo > a.count) blo = a.count;
     if (bhi > a.count) bhi = a.count;
     const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
@@ -309,13 +310,14 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * U;
   const uint32_t W = a.W;
+  const bool whole = a.mode == 4;  // Broadcast: one block, the root's whole vector
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, W, a.chunk, tile);
-    const uint32_t c = p.d;
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
     const uint32_t len = tile_len(p, a.B, a.chunk, tile);
     if (len == 0) continue;
     const char* s = a.src[c] + p.lo * ES;
-    const uint64_t voff = ((uint64_t)c * a.B + p.lo) * ES;
+    const uint64_t voff = ((whole ? 0 : (uint64_t)c * a.B) + p.lo) * ES;
     const uint32_t nvec = len / VE;
     u32x4 v[U];
 #pragma unroll
@@ -350,10 +352,13 @@ __global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const
   typedef typename Wire<DT>::elem_t elem_t;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t W = a.W;
+  const bool whole = a.mode >= 3;  // Reduce / Broadcast: one block, the whole vector, owned by the root
+  const bool one_src = a.mode == 2 || a.mode == 4;
+  const bool one_dst = a.mode == 1 || a.mode == 3;
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, W, a.chunk, tile);
-    const uint32_t c = p.d;
-    uint64_t blo = (uint64_t)c * a.B, bhi = blo + a.B;
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
     if (blo > a.count) blo = a.count;
     if (bhi > a.count) bhi = a.count;
     const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
@@ -362,14 +367,14 @@ __global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const
     for (uint32_t e = tid; e < len; e += nthr) {
       const uint64_t i = p.lo + e;  // inside block c
       elem_t acc;
-      if (a.mode == 2) {
+      if (one_src) {
         acc = reinterpret_cast<const elem_t*>(a.src[c])[i];
       } else {
         acc = reinterpret_cast<const elem_t*>(a.src[a.order[(pc + 1) % W]])[blo + i];
         for (uint32_t k = 2; k <= W; ++k)
           acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(a.src[a.order[(pc + k) % W]])[blo + i]);
       }
-      if (a.mode == 1) {
+      if (one_dst) {
         reinterpret_cast<elem_t*>(a.dst[c])[i] = acc;
       } else {
         for (uint32_t r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r])[blo + i] = acc;
@@ -434,11 +439,11 @@ static int launch_fused_d(const FusedArgs& a, const Tuning& t, hipStream_t s) {
   const dim3 g(t.blocks), b(t.threads);
   if (!t.vec) {
     const uint32_t es = sizeof(typename Wire<DT>::elem_t);
-    const int U = a.mode == 2 ? 4 : fused_unroll_c((int)a.W);
+    const int U = (a.mode == 2 || a.mode == 4) ? 4 : fused_unroll_c((int)a.W);
     ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U));
     return (int)hipGetLastError();
   }
-  if (a.mode == 2) {
+  if (a.mode == 2 || a.mode == 4) {
     constexpr int ES = sizeof(typename Wire<DT>::elem_t);
     if (t.nontemporal) gather_fused_vec<ES, true><<<g, b, 0, s>>>(a);
     else gather_fused_vec<ES, false><<<g, b, 0, s>>>(a);

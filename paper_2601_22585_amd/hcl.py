@@ -18,7 +18,7 @@ FP32, BF16, FP16, INT32 = 0, 1, 2, 3
 SUM = 0
 SCHED_STEPWISE, SCHED_FUSED = 0, 1
 XPORT_DIRECT, XPORT_HOST_STAGED = 0, 1
-KIND_ALLREDUCE, KIND_REDUCE_SCATTER, KIND_ALL_GATHER = 0, 1, 2
+KIND_ALLREDUCE, KIND_REDUCE_SCATTER, KIND_ALL_GATHER, KIND_REDUCE, KIND_BROADCAST, KIND_ALLTOALL = range(6)
 PHASE_RS, PHASE_AG = 0, 1
 MAX_RANKS = 16
 
@@ -27,7 +27,8 @@ SCHED = {"stepwise": SCHED_STEPWISE, "fused": SCHED_FUSED}
 XPORT = {"direct": XPORT_DIRECT, "host_staged": XPORT_HOST_STAGED}
 
 EXPORTS = [
-    "hcl_allreduce_sim", "hcl_reduce_scatter_sim", "hcl_all_gather_sim", "hcl_workspace_bytes",
+    "hcl_allreduce_sim", "hcl_reduce_scatter_sim", "hcl_all_gather_sim", "hcl_reduce_sim",
+    "hcl_broadcast_sim", "hcl_alltoall_sim", "hcl_workspace_bytes",
     "hcl_host_stage_bytes", "hcl_ring_step", "hcl_schedule_items", "hcl_events_create",
     "hcl_events_destroy", "hcl_event_record", "hcl_event_elapsed_ms", "hcl_device_cu_count",
     "hcl_status_string", "hcl_last_error", "hcl_version",
@@ -89,6 +90,11 @@ def lib():
     L.hcl_reduce_scatter_sim.argtypes = L.hcl_allreduce_sim.argtypes
     L.hcl_all_gather_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
                                      ctypes.c_size_t, op, ctypes.c_void_p]
+    L.hcl_reduce_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                 ctypes.c_size_t, op, ctypes.c_void_p]
+    L.hcl_broadcast_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_size_t, op, ctypes.c_void_p]
+    L.hcl_alltoall_sim.argtypes = L.hcl_all_gather_sim.argtypes
     for f in ("hcl_workspace_bytes", "hcl_host_stage_bytes"):
         getattr(L, f).argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_size_t, op]
         getattr(L, f).restype = ctypes.c_size_t
@@ -200,7 +206,7 @@ def _dtype_code(tensors, dtype):
 
 
 def _ptrs(tensors):
-    return _ptr_array([t.data_ptr() for t in tensors])
+    return _ptr_array([None if t is None else t.data_ptr() for t in tensors])
 
 
 def allreduce_sim(send, recv, chunk_bytes=0, dtype=None, op=SUM, stream=None, count=None, **opt):
@@ -230,6 +236,36 @@ def all_gather_sim(send, recv, chunk_bytes=0, dtype=None, stream=None, sendcount
     n = send[0].numel() if sendcount is None else sendcount
     _check(lib().hcl_all_gather_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype),
                                     chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
+    return o.n_launches.contents.value
+
+
+def reduce_sim(send, recv, root, chunk_bytes=0, dtype=None, op=SUM, stream=None, count=None, **opt):
+    """Ring Reduce (sum) to `root`: only recv[root] is written (other entries may be None)."""
+    W = len(send)
+    o, keep = make_opts(W, **opt)
+    n = send[0].numel() if count is None else count
+    _check(lib().hcl_reduce_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), op, root,
+                                chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
+    return o.n_launches.contents.value
+
+
+def broadcast_sim(send, recv, root, chunk_bytes=0, dtype=None, stream=None, count=None, **opt):
+    """Ring Broadcast from `root`: only send[root] is read (other entries may be None)."""
+    W = len(recv)
+    o, keep = make_opts(W, **opt)
+    n = recv[0].numel() if count is None else count
+    _check(lib().hcl_broadcast_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(recv, dtype), root,
+                                   chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
+    return o.n_launches.contents.value
+
+
+def alltoall_sim(send, recv, chunk_bytes=0, dtype=None, stream=None, count=None, **opt):
+    """All-to-All: block q of recv[r] becomes block r of send[q]; count = elements per block."""
+    W = len(send)
+    o, keep = make_opts(W, **opt)
+    n = send[0].numel() // W if count is None else count
+    _check(lib().hcl_alltoall_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype),
+                                  chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
     return o.n_launches.contents.value
 
 

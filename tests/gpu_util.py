@@ -128,3 +128,61 @@ def run_all_gather(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, inplace=
     for r in range(W):
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
     return nl
+
+
+def _to_dev(t, misalign=0):
+    base = torch.empty(t.numel() + misalign + 64, dtype=t.dtype, device="cuda")
+    d = base[misalign:misalign + t.numel()]
+    d.copy_(t)
+    return d
+
+
+def run_reduce(cfg_id, W, count, dtype, dist, root, ring=None, chunk_bytes=0, inplace=False, misalign=0, **opt):
+    cpu = wl.make_inputs(cfg_id, W, count, dtype, dist)
+    dev = [_to_dev(t, misalign) for t in cpu]
+    want = orc.reduce([wl.to_wire(t) for t in cpu], CODE[dtype], root, ring=ring, chunk_elems=chunk_bytes // wl.ESIZE[dtype])
+    wsb = hcl.workspace_bytes(hcl.KIND_REDUCE, W, count, CODE[dtype], chunk_bytes, sched=opt.get("sched", "stepwise"))
+    if wsb:
+        opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    recv = [None] * W
+    recv[root] = dev[root] if inplace else fresh(1, count, dtype, misalign, fill=0)[0]
+    n = hcl.reduce_sim(dev, recv, root, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"reduce W={W} count={count} {dtype} root={root} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')}"
+    assert_same_bits(recv[root], want, dtype, tag)
+    for r in range(W):
+        if not (inplace and r == root):
+            assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    return n
+
+
+def run_broadcast(cfg_id, W, count, dtype, dist, root, ring=None, chunk_bytes=0, inplace=False, misalign=0, **opt):
+    src = wl.make_inputs(cfg_id, 1, count, dtype, dist)[0]
+    want = orc.broadcast(wl.to_wire(src), CODE[dtype], W, root, ring=ring)
+    recv = fresh(W, count, dtype, misalign, fill=0)
+    send = [None] * W
+    if inplace:
+        recv[root].copy_(src)
+        send[root] = recv[root]
+    else:
+        send[root] = _to_dev(src, misalign)
+    n = hcl.broadcast_sim(send, recv, root, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"broadcast W={W} count={count} {dtype} root={root} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')}"
+    for r in range(W):
+        assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+    return n
+
+
+def run_alltoall(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, misalign=0, **opt):
+    cpu = wl.make_inputs(cfg_id, W, W * n, dtype, dist)
+    dev = [_to_dev(t, misalign) for t in cpu]
+    want = orc.alltoall([wl.to_wire(t) for t in cpu], CODE[dtype])
+    recv = fresh(W, W * n, dtype, misalign, fill=0)
+    nl = hcl.alltoall_sim(dev, recv, chunk_bytes=chunk_bytes, ring=ring, **opt)
+    torch.cuda.synchronize()
+    tag = f"alltoall W={W} n={n} {dtype} ring={ring} chunk={chunk_bytes} mis={misalign} {opt.get('sched')}"
+    for r in range(W):
+        assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+        assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    return nl

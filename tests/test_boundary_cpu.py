@@ -186,3 +186,27 @@ def test_schedule_items_cover_every_block_exactly_once(W, count, chunk_elems):
                     assert off == pos
                     pos += n
                 assert pos == blk(c)[1] - blk(c)[0]
+
+
+def test_other_collectives_validation_codes():
+    L = hcl.lib()
+    s, r = bufs(4), bufs(4, base=BASE * 2)
+    ps, pr = (ctypes.c_void_p * 4)(*s), (ctypes.c_void_p * 4)(*r)
+    o, keep = hcl.make_opts(4)
+    # count 0 is a no-op for all three
+    assert L.hcl_reduce_sim(ps, pr, 4, 0, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.OK
+    assert L.hcl_broadcast_sim(ps, pr, 4, 0, hcl.FP32, 0, 0, ctypes.byref(o), None) == hcl.OK
+    assert L.hcl_alltoall_sim(ps, pr, 4, 0, hcl.FP32, 0, ctypes.byref(o), None) == hcl.OK
+    # bad root, bad op, missing workspace, staged transport, aliasing
+    assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, hcl.SUM, 4, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
+    assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, 1, 0, 0, ctypes.byref(o), None) == hcl.ERR_UNSUPPORTED
+    assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_WORKSPACE
+    assert L.hcl_broadcast_sim(ps, pr, 4, 16, hcl.FP32, -1, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
+    st, keep2 = hcl.make_opts(4, xport="host_staged")
+    assert L.hcl_alltoall_sim(ps, pr, 4, 16, hcl.FP32, 0, ctypes.byref(st), None) == hcl.ERR_UNSUPPORTED
+    assert L.hcl_alltoall_sim(ps, ps, 4, 16, hcl.FP32, 0, ctypes.byref(o), None) == hcl.ERR_ALIAS
+    pr_null = (ctypes.c_void_p * 4)(None, r[1], r[2], r[3])
+    assert L.hcl_reduce_sim(ps, pr_null, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * ((1 << 21) + 65536 + 256)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16, sched="fused") == 0
+    assert hcl.workspace_bytes(hcl.KIND_BROADCAST, 8, 1 << 20, hcl.BF16) == 0
