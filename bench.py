@@ -69,7 +69,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 41, 5])
-    ap.add_argument("--op", default=None, choices=["allreduce", "reduce_scatter", "all_gather"],
+    ap.add_argument("--op", default=None, choices=["allreduce", "reduce_scatter", "all_gather", "reduce", "broadcast", "alltoall"],
                     help="collective to time (default: the config's; config 4 times reduce_scatter unless told otherwise)")
     ap.add_argument("--sched", default="stepwise", choices=["stepwise", "fused"])
     ap.add_argument("--fuse-rs-ag", action="store_true")
@@ -166,16 +166,38 @@ def main():
             wsb = hcl.workspace_bytes(kind, W, B, code, chunk_bytes, sched=args.sched, xport=xport)
             if wsb:
                 opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
-    else:
+    elif op == "all_gather":
         recv = [new(count) for _ in range(W)]
         send = [recv[r][r * B:(r + 1) * B] for r in range(W)] if args.inplace else [new(B) for _ in range(W)]
         kind = hcl.KIND_ALL_GATHER
         call = hcl.all_gather_sim
         per_call_count = B
+    elif op == "reduce":
+        send = [new(count) for _ in range(W)]
+        recv = [send[0] if args.inplace else new(count)] + [None] * (W - 1)
+        kind = hcl.KIND_REDUCE
+        call = lambda s_, r_, **kw: hcl.reduce_sim(s_, r_, 0, **kw)
+        per_call_count = count
+        wsb = hcl.workspace_bytes(kind, W, count, code, chunk_bytes, sched=args.sched)
+        if wsb:
+            opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    elif op == "broadcast":
+        recv = [new(count) for _ in range(W)]
+        send = [recv[0] if args.inplace else new(count)] + [None] * (W - 1)
+        kind = hcl.KIND_BROADCAST
+        call = lambda s_, r_, **kw: hcl.broadcast_sim(s_, r_, 0, **kw)
+        per_call_count = count
+    else:
+        send = [new(count) for _ in range(W)]
+        recv = [new(count) for _ in range(W)]
+        kind = hcl.KIND_ALLTOALL
+        call = hcl.alltoall_sim
+        per_call_count = B
 
     def refill():
         for r in range(W):
-            wl.fill_rank(send[r], wl.rank_seed(args.config, r), cfg["dist"])
+            if send[r] is not None:
+                wl.fill_rank(send[r], wl.rank_seed(args.config, r), cfg["dist"])
 
     refill()
     if xport == "host_staged":
@@ -194,9 +216,14 @@ def main():
         ce = min(chunk_bytes // es, m) if chunk_bytes else 0
         if op == "all_gather":
             ins = [wl.to_wire(send[r][:m]) for r in range(W)]
+        elif op == "broadcast":
+            ins = [np.concatenate([wl.to_wire(send[0][lo:hi]) for lo, hi in win])]
         else:
             ins = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in win]) for r in range(W)]
-        fn = {"allreduce": orc.allreduce, "reduce_scatter": orc.reduce_scatter, "all_gather": orc.all_gather}[op]
+        fn = {"allreduce": orc.allreduce, "reduce_scatter": orc.reduce_scatter, "all_gather": orc.all_gather,
+              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce(a, c_, 0, chunk_elems=chunk_elems)],
+              "broadcast": lambda a, c_, chunk_elems=0: orc.broadcast(a[0], c_, W, 0),
+              "alltoall": lambda a, c_, chunk_elems=0: orc.alltoall(a, c_)}[op]
         # one thread first, on an eighth of the sample, then every host core on all of it
         m1 = max(1, m // 8)
         if op == "all_gather":
@@ -223,7 +250,7 @@ def main():
                                        "sample_MiB_per_rank": round(W * m1 * es / 2**20, 2), "seconds": round(t_one, 3)}}
 
     def check_first_run():
-        for r in range(W):
+        for r in range(1 if op == "reduce" else W):
             if op == "reduce_scatter":
                 got = wl.to_wire(recv[r][:m])
             else:
@@ -233,7 +260,7 @@ def main():
         cpu_baseline["parity"] = "bit-exact on the sample"
 
     # ---- warm-up (the first run is also checked against the oracle sample) ----
-    clobbers = args.inplace and op != "all_gather"
+    clobbers = args.inplace and op in ("allreduce", "reduce_scatter", "reduce")
     launches = 0
     for i in range(max(1, args.warmup)):
         launches = call(send, recv, chunk_bytes=chunk_bytes, **opt)
@@ -280,10 +307,24 @@ def main():
     # ---- algorithmic bytes: of the whole call, and of one launch of the dominant kernel ----
     staged = xport == "host_staged"
     fuse = bool(opt.get("fuse_rs_ag")) and not staged
-    if args.sched == "fused":
-        kernel = f"ring_fused_vec<{dtype},W={W}>" if op != "all_gather" else "gather_fused_vec"
-        call_bytes = {"allreduce": 2 * W * S, "reduce_scatter": (W + 1) * S, "all_gather": (W + 1) * S}[op]
+    if op == "alltoall":
+        # every rank's W blocks read once and written once; a stepwise launch moves one block per rank
+        kernel = "reduce_copy_vec<copy,NSRC=1,NDST=1>"
+        call_bytes = 2 * W * S
+        bytes_per_launch = call_bytes / launches
+        n_dom, dom, units = launches, list(range(launches)), float(launches)
+    elif args.sched == "fused":
+        kernel = f"ring_fused_vec<{dtype},W={W}>" if op in ("allreduce", "reduce_scatter", "reduce") else "gather_fused_vec"
+        call_bytes = 2 * W * S if op == "allreduce" else (W + 1) * S
         bytes_per_launch, n_dom, dom, units = call_bytes, 1, [0], 1.0
+    elif op == "broadcast":
+        # W - 1 hops of the whole vector (S read, S written each); out of place one more copy, in the first launch
+        kernel = "reduce_copy_vec<copy,NSRC=1,NDST=1>"
+        own_copy = 0 if args.inplace else 2 * S
+        call_bytes = 2 * (W - 1) * S + own_copy
+        bytes_per_launch = 2 * S
+        n_dom, dom = W - 1, list(range(1, launches))
+        units = (W - 1) + (0 if args.inplace else 1)
     elif op == "all_gather":
         kernel = "reduce_copy_vec<copy,NSRC=1,NDST=1>"
         # a step copies one block per rank: S bytes read and S written, all ranks together; out of

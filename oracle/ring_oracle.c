@@ -402,6 +402,93 @@ int orc_alltoall(const void *const *in, void *const *out, int W, size_t n, int d
     return ORC_OK;
 }
 
+/* ------------------------------------------------------------------ */
+/* reordered-class variant: binary32 accumulation, one final rounding   */
+/* ------------------------------------------------------------------ */
+/* The paper accepts collectives that differ in reduction order within
+   floating-point tolerance (Appendix E.2 "LLM Training Convergence").  This
+   variant keeps the ring's order of operands for block c (next(c), ..., c)
+   but carries the running sum in binary32 and rounds to the wire type once,
+   at the end.  For fp32 and int32 it equals the ring result.  It is a
+   different result from the per-hop ring for bf16 / fp16, within 2 ulp of the
+   correctly rounded exact sum in the cases the tests bound. */
+static void sum_fp32acc_run(const void *const *in, const int *order, int W, size_t off, size_t n,
+                            int dtype, void *out)
+{
+    ptrdiff_t i, nn = (ptrdiff_t)n;
+    if (dtype == ORC_FP32) {
+        float *o = (float *)out;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) {
+            float acc = ((const float *)in[order[0]])[off + i];
+            for (int k = 1; k < W; ++k) acc = acc + ((const float *)in[order[k]])[off + i];
+            o[i] = acc;
+        }
+    } else if (dtype == ORC_INT32) {
+        int32_t *o = (int32_t *)out;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) {
+            uint32_t acc = (uint32_t)((const int32_t *)in[order[0]])[off + i];
+            for (int k = 1; k < W; ++k) acc += (uint32_t)((const int32_t *)in[order[k]])[off + i];
+            o[i] = (int32_t)acc;
+        }
+    } else {
+        uint16_t *o = (uint16_t *)out;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) {
+            uint16_t x = ((const uint16_t *)in[order[0]])[off + i];
+            float acc = dtype == ORC_BF16 ? orc_bf16_to_f32(x) : orc_f16_to_f32(x);
+            for (int k = 1; k < W; ++k) {
+                x = ((const uint16_t *)in[order[k]])[off + i];
+                acc = acc + (dtype == ORC_BF16 ? orc_bf16_to_f32(x) : orc_f16_to_f32(x));
+            }
+            o[i] = dtype == ORC_BF16 ? orc_f32_to_bf16(acc) : orc_f32_to_f16(acc);
+        }
+    }
+}
+
+/* All-Reduce with binary32 accumulation: in[r] count elements (untouched),
+   out[r] count elements, identical for every rank. */
+int orc_allreduce_fp32acc(const void *const *in, void *const *out, int W, size_t count, int dtype,
+                          const int *ring)
+{
+    int pos[64], order[64];
+    if (!args_ok(W, dtype) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype), B = (count + (size_t)W - 1) / (size_t)W;
+    for (int c = 0; c < W; ++c) {
+        size_t lo, hi;
+        block_range(count, B, c, &lo, &hi);
+        for (int k = 0; k < W; ++k) order[k] = ring_at(ring, wrap(pos[c] + 1 + k, W));
+        sum_fp32acc_run(in, order, W, lo, hi - lo, dtype, (unsigned char *)out[0] + lo * es);
+    }
+    for (int r = 1; r < W; ++r) memcpy(out[r], out[0], count * es);
+    return ORC_OK;
+}
+
+/* Reduce-Scatter with binary32 accumulation: in[r] W*n elements, out[r] n elements (block r). */
+int orc_reduce_scatter_fp32acc(const void *const *in, void *const *out, int W, size_t n, int dtype,
+                               const int *ring)
+{
+    int pos[64], order[64];
+    if (!args_ok(W, dtype) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    for (int c = 0; c < W; ++c) {
+        for (int k = 0; k < W; ++k) order[k] = ring_at(ring, wrap(pos[c] + 1 + k, W));
+        sum_fp32acc_run(in, order, W, (size_t)c * n, n, dtype, out[c]);
+    }
+    return ORC_OK;
+}
+
+/* Reduce to root with binary32 accumulation: in[r] count elements, out count elements. */
+int orc_reduce_fp32acc(const void *const *in, void *out, int W, size_t count, int dtype,
+                       const int *ring, int root)
+{
+    int pos[64], order[64];
+    if (!args_ok(W, dtype) || root < 0 || root >= W || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    for (int k = 0; k < W; ++k) order[k] = ring_at(ring, wrap(pos[root] + 1 + k, W));
+    sum_fp32acc_run(in, order, W, 0, count, dtype, out);
+    return ORC_OK;
+}
+
 /* bulk conversions, for the conversion pins */
 void orc_f32_to_bf16_n(const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_bf16(x[i]); }
 void orc_f32_to_f16_n (const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_f16(x[i]); }

@@ -52,6 +52,9 @@ def lib():
         L.orc_reduce.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int, ctypes.c_size_t]
         L.orc_broadcast.argtypes = [ctypes.c_void_p, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int]
         L.orc_alltoall.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int]
+        L.orc_allreduce_fp32acc.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip]
+        L.orc_reduce_scatter_fp32acc.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip]
+        L.orc_reduce_fp32acc.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int]
         L.orc_set_threads.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
@@ -168,6 +171,36 @@ def alltoall(inputs, dtype):
     assert total % W == 0 and all(s.size == total for s in src)
     out = [np.zeros(total, dtype=NP_WIRE[dtype]) for _ in range(W)]
     _check(lib().orc_alltoall(_ptrs(src), _ptrs(out), W, total // W, dtype), "alltoall")
+    return out
+
+
+def allreduce_fp32acc(inputs, dtype, ring=None):
+    """All-Reduce with binary32 accumulation in ring order and one final rounding."""
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    n = src[0].size
+    out = [np.zeros(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_allreduce_fp32acc(_ptrs(src), _ptrs(out), W, n, dtype, _ring_arg(ring, W)), "allreduce_fp32acc")
+    return out
+
+
+def reduce_scatter_fp32acc(inputs, dtype, ring=None):
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    total = src[0].size
+    assert total % W == 0
+    out = [np.zeros(total // W, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_reduce_scatter_fp32acc(_ptrs(src), _ptrs(out), W, total // W, dtype, _ring_arg(ring, W)),
+           "reduce_scatter_fp32acc")
+    return out
+
+
+def reduce_fp32acc(inputs, dtype, root, ring=None):
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    out = np.zeros(src[0].size, dtype=NP_WIRE[dtype])
+    _check(lib().orc_reduce_fp32acc(_ptrs(src), out.ctypes.data, W, src[0].size, dtype, _ring_arg(ring, W), root),
+           "reduce_fp32acc")
     return out
 
 

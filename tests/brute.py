@@ -151,3 +151,29 @@ def reduce(inputs, fmt, root, ring=None):
             acc = hop_int32(acc, inputs[r][i]) if fmt == "int32" else hop(acc, inputs[r][i], fmt)
         out.append(acc)
     return out
+
+
+def sum_fp32acc(bits_in_order, fmt):
+    """Binary32 running sum of the given wire values, in order, rounded to fmt once at the end."""
+    acc = widen(bits_in_order[0], fmt)
+    for b in bits_in_order[1:]:
+        acc = add_round(acc, widen(b, fmt), "fp32", "fp32")
+    d = decode(acc, "fp32")
+    eb, fb = FMT[fmt]
+    if d[0] == "nan":
+        return (((1 << eb) - 1) << fb) | (1 << (fb - 1))
+    if d[0] == "inf":
+        return (d[1] << (eb + fb)) | (((1 << eb) - 1) << fb)
+    return encode(d[1], d[2], fmt)
+
+
+def allreduce_fp32acc(inputs, fmt, ring=None):
+    W = len(inputs)
+    count = len(inputs[0])
+    ring = list(range(W)) if ring is None else list(ring)
+    out = [None] * count
+    for c, (lo, hi) in enumerate(block_ranges(count, W)):
+        order = fold_order(c, ring)
+        for i in range(lo, hi):
+            out[i] = sum_fp32acc([inputs[r][i] for r in order], fmt)
+    return out
