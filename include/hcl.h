@@ -90,6 +90,14 @@ typedef enum { HCL_SCHED_STEPWISE = 0, HCL_SCHED_FUSED = 1 } hcl_sched_t;
  *   RDMA"; Appendix F.1), local operands and results stay in device memory. */
 typedef enum { HCL_XPORT_DIRECT = 0, HCL_XPORT_HOST_STAGED = 1 } hcl_xport_t;
 
+/* PER_HOP: the ring's arithmetic, every addition rounded to the wire type.
+ * FP32 (FUSED sums only): the same order of operands, but the running sum
+ *   stays in binary32 and is rounded to the wire type once.  For bf16 / fp16
+ *   this is a DIFFERENT result from the ring's -- the reordered class the
+ *   paper tolerates between backends (Appendix E.2) -- within 2 ulp of the
+ *   correctly rounded exact sum; for fp32 and int32 it is the ring's result. */
+typedef enum { HCL_ACC_PER_HOP = 0, HCL_ACC_FP32 = 1 } hcl_acc_t;
+
 typedef enum {
   HCL_KIND_ALLREDUCE = 0, HCL_KIND_REDUCE_SCATTER = 1, HCL_KIND_ALL_GATHER = 2,
   HCL_KIND_REDUCE = 3, HCL_KIND_BROADCAST = 4, HCL_KIND_ALLTOALL = 5
@@ -124,6 +132,7 @@ typedef struct hcl_opts {
                               before the first All-Gather launch of an All-Reduce, the next one
                               after the last launch: the cheap way to time a phase's launches   */
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
+  int accumulate;          /* hcl_acc_t; anything but PER_HOP needs sched == FUSED           */
 } hcl_opts_t;
 
 /* One unit of the ring schedule, as hcl_schedule_items reports it. */

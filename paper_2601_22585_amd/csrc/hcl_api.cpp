@@ -228,6 +228,11 @@ struct Ctx {
     if (sched == HCL_SCHED_FUSED && xport == HCL_XPORT_HOST_STAGED)
       return fail(HCL_ERR_UNSUPPORTED, "the fused schedule has no staged transport: no block travels between ranks");
     fuse_rs_ag = o && o->fuse_rs_ag;
+    const int acc = o ? o->accumulate : 0;
+    if (acc != HCL_ACC_PER_HOP && acc != HCL_ACC_FP32) return fail(HCL_ERR_UNSUPPORTED, "unknown accumulate mode %d", acc);
+    if (acc == HCL_ACC_FP32 && sched != HCL_SCHED_FUSED)
+      return fail(HCL_ERR_UNSUPPORTED, "binary32 accumulation exists for the fused schedule only: in a stepwise ring the partial travels in the wire type");
+    tune.wide_acc = acc == HCL_ACC_FP32;
     if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
     if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
     phase_events = o && o->events_per_phase;

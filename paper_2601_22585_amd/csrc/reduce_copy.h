@@ -51,6 +51,7 @@ struct Tuning {
   int unroll;       // 1, 2, 4, 8
   bool nontemporal;
   bool vec;         // 128-bit path allowed (all addresses 16-byte aligned)
+  bool wide_acc;    // fused sums: binary32 accumulation, one final rounding (two-byte float types)
 };
 
 // Elements one tile covers for this dtype / tuning (vector path or not, same figure).

@@ -60,18 +60,33 @@ __device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
 
 template <int DT> struct Wire;
 
+// kWide: the type has a binary32-accumulation variant that differs from the
+// per-hop one (two-byte floats); widen2 / narrow2 split a word into its two
+// elements as binary32 and pack two binary32 values back with one rounding.
 template <> struct Wire<DT_FP32> {
   typedef uint32_t elem_t;
+  static constexpr bool kWide = false;
   __device__ static __forceinline__ uint32_t hop_word(uint32_t in, uint32_t loc) { return f2u(u2f(in) + u2f(loc)); }
   __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) { return hop_word(in, loc); }
+  __device__ static __forceinline__ void widen2(uint32_t, float&, float&) {}
+  __device__ static __forceinline__ uint32_t narrow2(float, float) { return 0; }
 };
 template <> struct Wire<DT_INT32> {
   typedef uint32_t elem_t;
+  static constexpr bool kWide = false;
   __device__ static __forceinline__ uint32_t hop_word(uint32_t in, uint32_t loc) { return in + loc; }
   __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) { return in + loc; }
+  __device__ static __forceinline__ void widen2(uint32_t, float&, float&) {}
+  __device__ static __forceinline__ uint32_t narrow2(float, float) { return 0; }
 };
 template <> struct Wire<DT_BF16> {
   typedef uint16_t elem_t;
+  static constexpr bool kWide = true;
+  __device__ static __forceinline__ void widen2(uint32_t w, float& lo, float& hi) {
+    lo = u2f(w << 16);
+    hi = u2f(w & 0xFFFF0000u);
+  }
+  __device__ static __forceinline__ uint32_t narrow2(float lo, float hi) { return bf16_pack_rne(lo, hi); }
   __device__ static __forceinline__ uint32_t hop_word(uint32_t in, uint32_t loc) {
     const float lo = u2f(in << 16) + u2f(loc << 16);
     const float hi = u2f(in & 0xFFFF0000u) + u2f(loc & 0xFFFF0000u);
@@ -84,6 +99,14 @@ template <> struct Wire<DT_BF16> {
 };
 template <> struct Wire<DT_FP16> {
   typedef uint16_t elem_t;
+  static constexpr bool kWide = true;
+  __device__ static __forceinline__ void widen2(uint32_t w, float& lo, float& hi) {
+    lo = widen((uint16_t)(w & 0xFFFFu));
+    hi = widen((uint16_t)(w >> 16));
+  }
+  __device__ static __forceinline__ uint32_t narrow2(float lo, float hi) {
+    return (uint32_t)narrow(lo) | ((uint32_t)narrow(hi) << 16);
+  }
   __device__ static __forceinline__ float widen(uint16_t h) {
     _Float16 x;
     __builtin_memcpy(&x, &h, 2);
@@ -113,6 +136,44 @@ __device__ __forceinline__ u32x4 hop_vec(u32x4 in, u32x4 loc) {
   r.z = Wire<DT>::hop_word(in.z, loc.z);
   r.w = Wire<DT>::hop_word(in.w, loc.w);
   return r;
+}
+
+// Sum of W vectors in order with binary32 accumulation and one final rounding
+// (two-byte float types only).
+template <int DT, int W>
+__device__ __forceinline__ u32x4 sum_wide(const u32x4 (&v)[W]) {
+  float acc[8];
+  Wire<DT>::widen2(v[0].x, acc[0], acc[1]);
+  Wire<DT>::widen2(v[0].y, acc[2], acc[3]);
+  Wire<DT>::widen2(v[0].z, acc[4], acc[5]);
+  Wire<DT>::widen2(v[0].w, acc[6], acc[7]);
+#pragma unroll
+  for (int k = 1; k < W; ++k) {
+    float t[8];
+    Wire<DT>::widen2(v[k].x, t[0], t[1]);
+    Wire<DT>::widen2(v[k].y, t[2], t[3]);
+    Wire<DT>::widen2(v[k].z, t[4], t[5]);
+    Wire<DT>::widen2(v[k].w, t[6], t[7]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = acc[j] + t[j];
+  }
+  u32x4 r;
+  r.x = Wire<DT>::narrow2(acc[0], acc[1]);
+  r.y = Wire<DT>::narrow2(acc[2], acc[3]);
+  r.z = Wire<DT>::narrow2(acc[4], acc[5]);
+  r.w = Wire<DT>::narrow2(acc[6], acc[7]);
+  return r;
+}
+// the same for one element: element e of a word-pair is widened through widen2
+template <int DT>
+__device__ __forceinline__ float widen1(typename Wire<DT>::elem_t x) {
+  float lo, hi;
+  Wire<DT>::widen2((uint32_t)x, lo, hi);
+  return lo;
+}
+template <int DT>
+__device__ __forceinline__ typename Wire<DT>::elem_t narrow1(float f) {
+  return (typename Wire<DT>::elem_t)(Wire<DT>::narrow2(f, 0.0f) & 0xFFFFu);
 }
 
 // ---------------------------------------------------------------------------
@@ -236,7 +297,7 @@ __global__ void __launch_bounds__(1024) reduce_copy_elem(const StepArgs a, const
 // ---------------------------------------------------------------------------
 __host__ __device__ constexpr int fused_unroll_c(int W) { return W <= 2 ? 4 : (W <= 4 ? 4 : (W <= 8 ? 2 : 1)); }
 
-template <int DT, int W, bool NT>
+template <int DT, int W, bool NT, bool WIDE>
 __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
@@ -276,9 +337,14 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
     for (int u = 0; u < U; ++u) {
       const uint32_t vi = u * nthr + tid;
       if (vi < nvec) {
-        u32x4 acc = v[u][0];
+        u32x4 acc;
+        if (WIDE) {
+          acc = sum_wide<DT, W>(v[u]);
+        } else {
+          acc = v[u][0];
 #pragma unroll
-        for (int k = 1; k < W; ++k) acc = hop_vec<DT>(acc, v[u][k]);
+          for (int k = 1; k < W; ++k) acc = hop_vec<DT>(acc, v[u][k]);
+        }
         if (to_all) {
 #pragma unroll
           for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
@@ -290,8 +356,15 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
     const uint32_t e = nvec * VE + tid;
     if (e < len) {
       elem_t acc = reinterpret_cast<const elem_t*>(sp[0])[e];
+      if (WIDE) {
+        float f = widen1<DT>(acc);
 #pragma unroll
-      for (int k = 1; k < W; ++k) acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(sp[k])[e]);
+        for (int k = 1; k < W; ++k) f = f + widen1<DT>(reinterpret_cast<const elem_t*>(sp[k])[e]);
+        acc = narrow1<DT>(f);
+      } else {
+#pragma unroll
+        for (int k = 1; k < W; ++k) acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(sp[k])[e]);
+      }
       if (to_all) {
 #pragma unroll
         for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
@@ -348,7 +421,7 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
 
 // Element-wise fused path (any alignment, any W, all three modes).
 template <int DT>
-__global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const uint32_t tile) {
+__global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const uint32_t tile, const bool wide) {
   typedef typename Wire<DT>::elem_t elem_t;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t W = a.W;
@@ -371,8 +444,15 @@ __global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const
         acc = reinterpret_cast<const elem_t*>(a.src[c])[i];
       } else {
         acc = reinterpret_cast<const elem_t*>(a.src[a.order[(pc + 1) % W]])[blo + i];
-        for (uint32_t k = 2; k <= W; ++k)
-          acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(a.src[a.order[(pc + k) % W]])[blo + i]);
+        if (Wire<DT>::kWide && wide) {
+          float f = widen1<DT>(acc);
+          for (uint32_t k = 2; k <= W; ++k)
+            f = f + widen1<DT>(reinterpret_cast<const elem_t*>(a.src[a.order[(pc + k) % W]])[blo + i]);
+          acc = narrow1<DT>(f);
+        } else {
+          for (uint32_t k = 2; k <= W; ++k)
+            acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(a.src[a.order[(pc + k) % W]])[blo + i]);
+        }
       }
       if (one_dst) {
         reinterpret_cast<elem_t*>(a.dst[c])[i] = acc;
@@ -440,7 +520,7 @@ static int launch_fused_d(const FusedArgs& a, const Tuning& t, hipStream_t s) {
   if (!t.vec) {
     const uint32_t es = sizeof(typename Wire<DT>::elem_t);
     const int U = (a.mode == 2 || a.mode == 4) ? 4 : fused_unroll_c((int)a.W);
-    ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U));
+    ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U), t.wide_acc);
     return (int)hipGetLastError();
   }
   if (a.mode == 2 || a.mode == 4) {
@@ -449,10 +529,17 @@ static int launch_fused_d(const FusedArgs& a, const Tuning& t, hipStream_t s) {
     else gather_fused_vec<ES, false><<<g, b, 0, s>>>(a);
     return (int)hipGetLastError();
   }
-#define HCL_CASE(WW)                                                          \
-  case WW:                                                                    \
-    if (t.nontemporal) ring_fused_vec<DT, WW, true><<<g, b, 0, s>>>(a);       \
-    else ring_fused_vec<DT, WW, false><<<g, b, 0, s>>>(a);                    \
+  constexpr bool kW = Wire<DT>::kWide;
+  const bool wide = kW && t.wide_acc;
+#define HCL_CASE(WW)                                                                      \
+  case WW:                                                                                \
+    if (wide) {                                                                           \
+      if (t.nontemporal) ring_fused_vec<DT, WW, true, kW><<<g, b, 0, s>>>(a);             \
+      else ring_fused_vec<DT, WW, false, kW><<<g, b, 0, s>>>(a);                          \
+    } else {                                                                              \
+      if (t.nontemporal) ring_fused_vec<DT, WW, true, false><<<g, b, 0, s>>>(a);          \
+      else ring_fused_vec<DT, WW, false, false><<<g, b, 0, s>>>(a);                       \
+    }                                                                                     \
     break;
   switch (a.W) {
     HCL_CASE(2) HCL_CASE(3) HCL_CASE(4) HCL_CASE(5) HCL_CASE(6) HCL_CASE(7) HCL_CASE(8) HCL_CASE(9)

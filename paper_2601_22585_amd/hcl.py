@@ -25,6 +25,8 @@ MAX_RANKS = 16
 DTYPE_OF_TORCH = {torch.float32: FP32, torch.bfloat16: BF16, torch.float16: FP16, torch.int32: INT32}
 SCHED = {"stepwise": SCHED_STEPWISE, "fused": SCHED_FUSED}
 XPORT = {"direct": XPORT_DIRECT, "host_staged": XPORT_HOST_STAGED}
+ACC_PER_HOP, ACC_FP32 = 0, 1
+ACC = {"per_hop": ACC_PER_HOP, "fp32": ACC_FP32}
 
 EXPORTS = [
     "hcl_allreduce_sim", "hcl_reduce_scatter_sim", "hcl_all_gather_sim", "hcl_reduce_sim",
@@ -59,6 +61,7 @@ class Opts(ctypes.Structure):
         ("n_events", ctypes.c_int),
         ("events_per_phase", ctypes.c_int),
         ("n_launches", ctypes.POINTER(ctypes.c_int)),
+        ("accumulate", ctypes.c_int),
     ]
 
 
@@ -163,7 +166,7 @@ class EventList:
 
 def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, host_stage=None,
               threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None,
-              events_per_phase=False):
+              events_per_phase=False, accumulate=0):
     """Builds the hcl_opts_t struct.  Returns (opts, keepalive): keep `keepalive`
     referenced until the call has returned."""
     o = Opts()
@@ -184,6 +187,7 @@ def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, ho
         keep.append(host_stage)
     o.threads, o.blocks, o.unroll, o.nontemporal = int(threads), int(blocks), int(unroll), int(nontemporal)
     o.fuse_rs_ag = 1 if fuse_rs_ag else 0
+    o.accumulate = ACC[accumulate] if isinstance(accumulate, str) else int(accumulate)
     if events is not None:
         # an EventList, or (EventList, first, n) to use a slice of it
         ev, first, n = events if isinstance(events, tuple) else (events, 0, events.n)

@@ -65,6 +65,8 @@ def test_allreduce_validation_codes():
     assert _call_ar(s, r, 4, 16, ring=[0, 1, 2, 2]) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 16, ring=[0, 1, 2, 4]) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 16, sched=5) == hcl.ERR_UNSUPPORTED
+    assert _call_ar(s, r, 4, 16, accumulate="fp32") == hcl.ERR_UNSUPPORTED     # stepwise has no such mode
+    assert _call_ar(s, r, 4, 16, sched="fused", accumulate=3) == hcl.ERR_UNSUPPORTED
     assert _call_ar(s, r, 4, 16, xport=5) == hcl.ERR_UNSUPPORTED
     assert _call_ar(s, r, 4, 16, threads=100) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 16, unroll=3) == hcl.ERR_INVALID_ARG
