@@ -73,6 +73,8 @@ def parse():
                     help="collective to time (default: the config's; config 4 times reduce_scatter unless told otherwise)")
     ap.add_argument("--sched", default="stepwise", choices=["stepwise", "fused"])
     ap.add_argument("--fuse-rs-ag", action="store_true")
+    ap.add_argument("--accumulate", default="per_hop", choices=["per_hop", "fp32"],
+                    help="fp32: fused sums with binary32 accumulation and one rounding (a reordered-class result)")
     ap.add_argument("--inplace", action="store_true")
     ap.add_argument("--bytes-per-rank", type=int, default=0, help="config 3: bytes per rank buffer")
     ap.add_argument("--shard-elems", type=int, default=0, help="config 4: elements per shard (default 2 GiB worth)")
@@ -149,6 +151,8 @@ def main():
 
     opt = dict(sched=args.sched, xport=xport, threads=args.threads, blocks=args.blocks, unroll=args.unroll,
                nontemporal=args.nontemporal)
+    if args.accumulate != "per_hop":
+        opt["accumulate"] = args.accumulate
     if op == "allreduce":
         opt["fuse_rs_ag"] = args.fuse_rs_ag
         send = [new(count) for _ in range(W)]
@@ -220,8 +224,12 @@ def main():
             ins = [np.concatenate([wl.to_wire(send[0][lo:hi]) for lo, hi in win])]
         else:
             ins = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in win]) for r in range(W)]
-        fn = {"allreduce": orc.allreduce, "reduce_scatter": orc.reduce_scatter, "all_gather": orc.all_gather,
-              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce(a, c_, 0, chunk_elems=chunk_elems)],
+        wide = args.accumulate == "fp32"
+        fn = {"allreduce": (lambda a, c_, chunk_elems=0: orc.allreduce_fp32acc(a, c_)) if wide else orc.allreduce,
+              "reduce_scatter": (lambda a, c_, chunk_elems=0: orc.reduce_scatter_fp32acc(a, c_)) if wide else orc.reduce_scatter,
+              "all_gather": orc.all_gather,
+              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce_fp32acc(a, c_, 0) if wide
+                                                      else orc.reduce(a, c_, 0, chunk_elems=chunk_elems)],
               "broadcast": lambda a, c_, chunk_elems=0: orc.broadcast(a[0], c_, W, 0),
               "alltoall": lambda a, c_, chunk_elems=0: orc.alltoall(a, c_)}[op]
         # one thread first, on an eighth of the sample, then every host core on all of it
@@ -385,7 +393,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
                    "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
-                   "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph)},
+                   "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph), "accumulate": args.accumulate},
         "algbw_rank_equiv_GBps": round(W * value, 2),
         "call_hbm_GBps": round(call_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "call_hbm_frac_of_peak": round(call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

@@ -24,8 +24,8 @@ struct StepArgs {
   uint32_t nseg;
   uint32_t tiles_per_chunk;
   uint32_t total_tiles;
-  uint32_t pad_;
-  uint64_t chunk;  // elements per chunk (> 0)
+  uint32_t stagger;  // segment d starts its walk through a chunk d * stagger tiles in (mod tiles_per_chunk)
+  uint64_t chunk;    // elements per chunk (> 0)
 };
 
 // Whole-collective launch: every element's ring pass stays in one thread.

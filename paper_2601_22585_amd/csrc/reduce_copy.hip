@@ -185,13 +185,17 @@ struct TilePos {
   uint64_t lo;  // first element inside the segment
 };
 
+// stagger: segment d takes the tiles of a chunk in rotated order, starting
+// d * stagger tiles in, so that segments whose base addresses are congruent
+// modulo a large power of two are not walked at the same offset at the same time
 __device__ __forceinline__ TilePos locate(uint32_t t, uint32_t tiles_per_chunk, uint32_t nseg,
-                                          uint64_t chunk, uint32_t tile) {
+                                          uint64_t chunk, uint32_t tile, uint32_t stagger = 0) {
   TilePos p;
-  const uint32_t k = t % tiles_per_chunk;
+  uint32_t k = t % tiles_per_chunk;
   const uint32_t q = t / tiles_per_chunk;
   p.d = q % nseg;
   p.j = q / nseg;
+  if (stagger) k = (k + p.d * stagger) % tiles_per_chunk;
   p.lo = p.j * chunk + (uint64_t)k * tile;
   return p;
 }
@@ -217,7 +221,7 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
   const uint32_t tile = nthr * VE * UNROLL;
 
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile);
+    const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile, a.stagger);
     const uint32_t len = tile_len(p, a.seg[p.d].n, a.chunk, tile);
     if (len == 0) continue;
 
@@ -273,7 +277,7 @@ __global__ void __launch_bounds__(1024) reduce_copy_elem(const StepArgs a, const
   typedef typename Wire<DT>::elem_t elem_t;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile);
+    const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile, a.stagger);
     const uint32_t len = tile_len(p, a.seg[p.d].n, a.chunk, tile);
     if (len == 0) continue;
     const elem_t* s0 = reinterpret_cast<const elem_t*>(a.seg[p.d].src0) + p.lo;
