@@ -17,7 +17,7 @@ buffers that are already resident in HBM.  Prints ONE JSON line:
   cpu_baseline the CPU oracle timed on a bounded sample of the same workload,
                whose result is also bit-compared with the GPU's first run
 
-Other workloads (reported in the design doc, not bench lines of their own):
+Other workloads (not bench lines of their own):
   --config 1            4 ranks, 1 MiB fp32
   --config 3 --bytes-per-rank N   fp16, 16 ranks, message-size sweep point
   --config 4 | 41       ZeRO-style Reduce-Scatter then All-Gather, bf16 | int32,
