@@ -40,6 +40,22 @@
  *   - A chunk is a contiguous run of chunk_elems elements inside a block.  It
  *     only orders the element loop; it never changes a value.
  *
+ *   - Reduction operators other than the sum (the call shape carries a
+ *     reduction operator, Section 4.4): one hop is
+ *         partial = round_T( op(f32(incoming), f32(local)) )
+ *     for the product (the product of two bf16 / fp16 values is exact in
+ *     binary32, so the hop is the correctly rounded product), and
+ *         partial = op(incoming, local)
+ *     for maximum / minimum, which follow IEEE 754-2019 clause 9.6: a NaN
+ *     operand gives NaN, and -0 orders below +0.  int32: the product wraps
+ *     modulo 2^32, maximum / minimum compare as signed integers.
+ *   - Tree order (a reordered-class variant, like binary32 accumulation): the
+ *     ranks' values are taken in ring order ring[0], ring[1], ..., ring[W-1] --
+ *     the same order for every block -- and combined level by level, neighbours
+ *     first: (v0 op v1), (v2 op v3), ...; an odd value at the end of a level
+ *     moves up unchanged.  Every node is rounded to the wire type (per-node
+ *     rounding) or the whole tree is evaluated in binary32 and rounded once.
+ *
  *   - Reduce / Broadcast travel along the same ring as chains that end
  *     (Reduce) or start (Broadcast) at the root; Reduce therefore sums in the
  *     order next(root), ..., root.  All-to-All is the plain block transpose.
@@ -67,6 +83,9 @@
 enum { ORC_FP32 = 0, ORC_BF16 = 1, ORC_FP16 = 2, ORC_INT32 = 3 };
 enum { ORC_OK = 0, ORC_BAD_ARG = 1, ORC_NO_MEM = 2 };
 enum { ORC_PHASE_RS = 0, ORC_PHASE_AG = 1 };
+enum { ORC_SUM = 0, ORC_PROD = 1, ORC_MAX = 2, ORC_MIN = 3 };
+enum { ORC_ORDER_RING = 0, ORC_ORDER_TREE = 1 };
+enum { ORC_ROUND_EACH = 0, ORC_ROUND_ONCE = 1 };
 
 /* ------------------------------------------------------------------ */
 /* bit views                                                           */
@@ -157,6 +176,82 @@ uint16_t orc_hop_f16 (uint16_t incoming, uint16_t local)
 int32_t  orc_hop_i32 (int32_t incoming, int32_t local)
 { return (int32_t)((uint32_t)incoming + (uint32_t)local); }
 
+/* ------------------------------------------------------------------ */
+/* the other reduction operators                                       */
+/* ------------------------------------------------------------------ */
+/* IEEE 754-2019 maximum / minimum on binary32 values: NaN if either operand
+   is NaN; of two zeros with different signs the maximum is +0, the minimum -0 */
+static float f32_maximum(float a, float b)
+{
+    if (isnan(a) || isnan(b)) return NAN;
+    if (a > b) return a;
+    if (b > a) return b;
+    return signbit(a) ? b : a;      /* equal values: differ at most in the sign of zero */
+}
+static float f32_minimum(float a, float b)
+{
+    if (isnan(a) || isnan(b)) return NAN;
+    if (a < b) return a;
+    if (b < a) return b;
+    return signbit(a) ? a : b;
+}
+/* op on two binary32 values, one IEEE operation, no rounding to a wire type */
+static float f32_apply(int op, float a, float b)
+{
+    switch (op) {
+    case ORC_PROD: return a * b;
+    case ORC_MAX:  return f32_maximum(a, b);
+    case ORC_MIN:  return f32_minimum(a, b);
+    default:       return a + b;
+    }
+}
+static int32_t i32_apply(int op, int32_t a, int32_t b)
+{
+    switch (op) {
+    case ORC_PROD: return (int32_t)((uint32_t)a * (uint32_t)b);
+    case ORC_MAX:  return a > b ? a : b;
+    case ORC_MIN:  return a < b ? a : b;
+    default:       return (int32_t)((uint32_t)a + (uint32_t)b);
+    }
+}
+/* widen a wire element to binary32 (exact) and round binary32 to the wire type */
+static float wire_to_f32(const void *p, size_t i, int dtype)
+{
+    if (dtype == ORC_FP32) return ((const float *)p)[i];
+    uint16_t h = ((const uint16_t *)p)[i];
+    return dtype == ORC_BF16 ? orc_bf16_to_f32(h) : orc_f16_to_f32(h);
+}
+static void f32_to_wire(void *p, size_t i, int dtype, float v)
+{
+    if (dtype == ORC_FP32) ((float *)p)[i] = v;
+    else ((uint16_t *)p)[i] = dtype == ORC_BF16 ? orc_f32_to_bf16(v) : orc_f32_to_f16(v);
+}
+/* round a binary32 value to the wire type and widen it again: the value a
+   partial has after it travelled in the wire type */
+static float through_wire(float v, int dtype)
+{
+    if (dtype == ORC_BF16) return orc_bf16_to_f32(orc_f32_to_bf16(v));
+    if (dtype == ORC_FP16) return orc_f16_to_f32(orc_f32_to_f16(v));
+    return v;
+}
+
+/* one hop with operator `op`, element-wise over a run: local[i] = round_T(op(inbox[i], local[i])) */
+static void hop_run_op(void *local, const void *inbox, size_t n, int dtype, int op)
+{
+    ptrdiff_t i, nn = (ptrdiff_t)n;
+    if (dtype == ORC_INT32) {
+        int32_t *l = (int32_t *)local; const int32_t *in = (const int32_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = i32_apply(op, in[i], l[i]);
+        return;
+    }
+    #pragma omp parallel for schedule(static) if (nn > 32768)
+    for (i = 0; i < nn; ++i) {
+        float a = wire_to_f32(inbox, (size_t)i, dtype), b = wire_to_f32(local, (size_t)i, dtype);
+        f32_to_wire(local, (size_t)i, dtype, f32_apply(op, a, b));
+    }
+}
+
 /* element-wise hop over a run: local[i] = hop(inbox[i], local[i]) */
 static void hop_run(void *local, const void *inbox, size_t n, int dtype)
 {
@@ -246,7 +341,7 @@ static void block_range(size_t count, size_t B, int c, size_t *lo, size_t *hi)
 /* the ring, as message passing over work[r] (count elements each)     */
 /* ------------------------------------------------------------------ */
 static int ring_phase(void *const *work, int W, size_t count, size_t B, int dtype,
-                      const int *ring, size_t chunk_elems, int phase)
+                      const int *ring, size_t chunk_elems, int phase, int op)
 {
     int pos[64], r, s;
     size_t es = orc_esize(dtype);
@@ -280,8 +375,9 @@ static int ring_phase(void *const *work, int W, size_t count, size_t B, int dtyp
                 size_t n = (len - c0 < C) ? len - c0 : C;
                 unsigned char *mine = (unsigned char *)work[r] + (lo + c0) * es;
                 const unsigned char *got = inbox[r] + c0 * es;
-                if (phase == ORC_PHASE_RS) hop_run(mine, got, n, dtype);
-                else                       copy_run(mine, got, n * es);
+                if (phase == ORC_PHASE_AG)   copy_run(mine, got, n * es);
+                else if (op == ORC_SUM)      hop_run(mine, got, n, dtype);
+                else                         hop_run_op(mine, got, n, dtype, op);
             }
         }
     }
@@ -291,33 +387,45 @@ static int ring_phase(void *const *work, int W, size_t count, size_t B, int dtyp
 }
 
 static int args_ok(int W, int dtype) { return W >= 1 && W <= 64 && dtype >= 0 && dtype <= 3; }
+static int op_ok(int op) { return op >= ORC_SUM && op <= ORC_MIN; }
 
-/* All-Reduce (sum), in place on work[r]: on entry rank r's input, on exit the
-   ring-order sum in every work[r]. */
+/* All-Reduce with operator `op`, in place on work[r]: on entry rank r's input,
+   on exit the ring-order reduction in every work[r]. */
+int orc_allreduce_op(void *const *work, int W, size_t count, int dtype, int op,
+                     const int *ring, size_t chunk_elems)
+{
+    if (!args_ok(W, dtype) || !op_ok(op)) return ORC_BAD_ARG;
+    size_t B = (count + (size_t)W - 1) / (size_t)W;
+    int rc = ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_RS, op);
+    if (rc) return rc;
+    return ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_AG, op);
+}
+/* All-Reduce (sum) */
 int orc_allreduce(void *const *work, int W, size_t count, int dtype,
                   const int *ring, size_t chunk_elems)
 {
-    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
-    size_t B = (count + (size_t)W - 1) / (size_t)W;
-    int rc = ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_RS);
-    if (rc) return rc;
-    return ring_phase(work, W, count, B, dtype, ring, chunk_elems, ORC_PHASE_AG);
+    return orc_allreduce_op(work, W, count, dtype, ORC_SUM, ring, chunk_elems);
 }
 
 /* Reduce-Scatter (sum): work[r] holds W*recvcount elements (rank r's full
    input; used as scratch, contents undefined on exit); out[r] receives
    recvcount elements = block r of the ring-order sum. */
-int orc_reduce_scatter(void *const *work, void *const *out, int W, size_t recvcount,
-                       int dtype, const int *ring, size_t chunk_elems)
+int orc_reduce_scatter_op(void *const *work, void *const *out, int W, size_t recvcount,
+                          int dtype, int op, const int *ring, size_t chunk_elems)
 {
-    if (!args_ok(W, dtype)) return ORC_BAD_ARG;
+    if (!args_ok(W, dtype) || !op_ok(op)) return ORC_BAD_ARG;
     int rc = ring_phase(work, W, (size_t)W * recvcount, recvcount, dtype, ring,
-                        chunk_elems, ORC_PHASE_RS);
+                        chunk_elems, ORC_PHASE_RS, op);
     if (rc) return rc;
     size_t es = orc_esize(dtype);
     for (int r = 0; r < W; ++r)
         memcpy(out[r], (const unsigned char *)work[r] + (size_t)r * recvcount * es, recvcount * es);
     return ORC_OK;
+}
+int orc_reduce_scatter(void *const *work, void *const *out, int W, size_t recvcount,
+                       int dtype, const int *ring, size_t chunk_elems)
+{
+    return orc_reduce_scatter_op(work, out, W, recvcount, dtype, ORC_SUM, ring, chunk_elems);
 }
 
 /* All-Gather: in[r] holds sendcount elements; out[r] (W*sendcount elements)
@@ -330,7 +438,7 @@ int orc_all_gather(const void *const *in, void *const *out, int W, size_t sendco
     for (int r = 0; r < W; ++r)   /* each rank starts with its own block in place */
         memcpy((unsigned char *)out[r] + (size_t)r * sendcount * es, in[r], sendcount * es);
     return ring_phase(out, W, (size_t)W * sendcount, sendcount, dtype, ring,
-                      chunk_elems, ORC_PHASE_AG);
+                      chunk_elems, ORC_PHASE_AG, ORC_SUM);
 }
 
 /* ------------------------------------------------------------------ */
@@ -345,11 +453,11 @@ int orc_all_gather(const void *const *in, void *const *out, int W, size_t sendco
    the root.  in[r]: count elements, untouched.  out: count elements, the
    root's result.  The fold order equals that of block `root` of the ring
    All-Reduce, applied to the whole vector. */
-int orc_reduce(const void *const *in, void *out, int W, size_t count, int dtype,
-               const int *ring, int root, size_t chunk_elems)
+int orc_reduce_op(const void *const *in, void *out, int W, size_t count, int dtype, int op,
+                  const int *ring, int root, size_t chunk_elems)
 {
     int pos[64];
-    if (!args_ok(W, dtype) || root < 0 || root >= W) return ORC_BAD_ARG;
+    if (!args_ok(W, dtype) || !op_ok(op) || root < 0 || root >= W) return ORC_BAD_ARG;
     if (!ring_ok(W, ring, pos)) return ORC_BAD_ARG;
     size_t es = orc_esize(dtype), C = chunk_elems ? chunk_elems : count, c0;
     unsigned char *msg = (unsigned char *)malloc(count * es + 1);
@@ -362,13 +470,19 @@ int orc_reduce(const void *const *in, void *out, int W, size_t count, int dtype,
         memcpy(mine, in[r], count * es);
         for (c0 = 0; c0 < count; c0 += C) {
             size_t n = (count - c0 < C) ? count - c0 : C;
-            hop_run(mine + c0 * es, msg + c0 * es, n, dtype);
+            if (op == ORC_SUM) hop_run(mine + c0 * es, msg + c0 * es, n, dtype);
+            else               hop_run_op(mine + c0 * es, msg + c0 * es, n, dtype, op);
         }
         memcpy(msg, mine, count * es);                      /* the partial travels on */
     }
     memcpy(out, msg, count * es);                           /* W == 1: the root's own vector */
     free(msg); free(mine);
     return ORC_OK;
+}
+int orc_reduce(const void *const *in, void *out, int W, size_t count, int dtype,
+               const int *ring, int root, size_t chunk_elems)
+{
+    return orc_reduce_op(in, out, W, count, dtype, ORC_SUM, ring, root, chunk_elems);
 }
 
 /* Broadcast from `root` along the ring: out[r] (count elements) becomes a copy
@@ -489,6 +603,125 @@ int orc_reduce_fp32acc(const void *const *in, void *out, int W, size_t count, in
     return ORC_OK;
 }
 
+/* ------------------------------------------------------------------ */
+/* reordered-class variants in general: operator, order, rounding       */
+/* ------------------------------------------------------------------ */
+/* Combines the W values v[0..W-1] (already in the order they enter) into one.
+   order RING: ((v0 op v1) op v2) ... op v[W-1].
+   order TREE: level by level, neighbours first; an odd last value moves up.
+   rounding EACH: every intermediate result travels in the wire type;
+   rounding ONCE: intermediates stay in binary32.  The caller rounds the
+   returned value to the wire type (a no-op after EACH). */
+static float combine_f32(float *v, int W, int dtype, int op, int order, int rounding)
+{
+    if (order == ORC_ORDER_RING) {
+        float acc = v[0];
+        for (int k = 1; k < W; ++k) {
+            acc = f32_apply(op, acc, v[k]);
+            if (rounding == ORC_ROUND_EACH) acc = through_wire(acc, dtype);
+        }
+        return acc;
+    }
+    int n = W;
+    while (n > 1) {
+        int m = 0;
+        for (int k = 0; k + 1 < n; k += 2) {
+            float t = f32_apply(op, v[k], v[k + 1]);
+            if (rounding == ORC_ROUND_EACH) t = through_wire(t, dtype);
+            v[m++] = t;
+        }
+        if (n & 1) v[m++] = v[n - 1];
+        n = m;
+    }
+    return v[0];
+}
+static int32_t combine_i32(int32_t *v, int W, int op, int order)
+{
+    if (order == ORC_ORDER_RING) {
+        int32_t acc = v[0];
+        for (int k = 1; k < W; ++k) acc = i32_apply(op, acc, v[k]);
+        return acc;
+    }
+    int n = W;
+    while (n > 1) {
+        int m = 0;
+        for (int k = 0; k + 1 < n; k += 2) v[m++] = i32_apply(op, v[k], v[k + 1]);
+        if (n & 1) v[m++] = v[n - 1];
+        n = m;
+    }
+    return v[0];
+}
+/* out[i] = combination of in[who[k]][off + i], k = 0..W-1, for i in [0, n) */
+static void combine_run(const void *const *in, const int *who, int W, size_t off, size_t n, int dtype,
+                        int op, int order, int rounding, void *out)
+{
+    ptrdiff_t i, nn = (ptrdiff_t)n;
+    #pragma omp parallel for schedule(static) if (nn > 32768)
+    for (i = 0; i < nn; ++i) {
+        if (dtype == ORC_INT32) {
+            int32_t v[64];
+            for (int k = 0; k < W; ++k) v[k] = ((const int32_t *)in[who[k]])[off + (size_t)i];
+            ((int32_t *)out)[i] = combine_i32(v, W, op, order);
+        } else {
+            float v[64];
+            for (int k = 0; k < W; ++k) v[k] = wire_to_f32(in[who[k]], off + (size_t)i, dtype);
+            f32_to_wire(out, (size_t)i, dtype, combine_f32(v, W, dtype, op, order, rounding));
+        }
+    }
+}
+/* the order in which the ranks' values enter block c (or the root's vector) */
+static void entry_order(int W, const int *ring, const int *pos, int c, int order, int *who)
+{
+    for (int k = 0; k < W; ++k)
+        who[k] = order == ORC_ORDER_RING ? ring_at(ring, wrap(pos[c] + 1 + k, W)) : ring_at(ring, k);
+}
+static int var_ok(int op, int order, int rounding)
+{
+    return op_ok(op) && (order == ORC_ORDER_RING || order == ORC_ORDER_TREE)
+        && (rounding == ORC_ROUND_EACH || rounding == ORC_ROUND_ONCE);
+}
+
+/* All-Reduce variant: in[r] count elements (untouched), out[r] count elements,
+   identical for every rank.  (RING, EACH) is the ring's own result. */
+int orc_allreduce_var(const void *const *in, void *const *out, int W, size_t count, int dtype,
+                      int op, const int *ring, int order, int rounding)
+{
+    int pos[64], who[64];
+    if (!args_ok(W, dtype) || !var_ok(op, order, rounding) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    size_t es = orc_esize(dtype), B = (count + (size_t)W - 1) / (size_t)W;
+    for (int c = 0; c < W; ++c) {
+        size_t lo, hi;
+        block_range(count, B, c, &lo, &hi);
+        entry_order(W, ring, pos, c, order, who);
+        combine_run(in, who, W, lo, hi - lo, dtype, op, order, rounding, (unsigned char *)out[0] + lo * es);
+    }
+    for (int r = 1; r < W; ++r) memcpy(out[r], out[0], count * es);
+    return ORC_OK;
+}
+/* Reduce-Scatter variant: in[r] W*n elements, out[r] n elements (block r). */
+int orc_reduce_scatter_var(const void *const *in, void *const *out, int W, size_t n, int dtype,
+                           int op, const int *ring, int order, int rounding)
+{
+    int pos[64], who[64];
+    if (!args_ok(W, dtype) || !var_ok(op, order, rounding) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    for (int c = 0; c < W; ++c) {
+        entry_order(W, ring, pos, c, order, who);
+        combine_run(in, who, W, (size_t)c * n, n, dtype, op, order, rounding, out[c]);
+    }
+    return ORC_OK;
+}
+/* Reduce-to-root variant: in[r] count elements, out count elements. */
+int orc_reduce_var(const void *const *in, void *out, int W, size_t count, int dtype,
+                   int op, const int *ring, int root, int order, int rounding)
+{
+    int pos[64], who[64];
+    if (!args_ok(W, dtype) || !var_ok(op, order, rounding) || root < 0 || root >= W
+        || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    entry_order(W, ring, pos, root, order, who);
+    combine_run(in, who, W, 0, count, dtype, op, order, rounding, out);
+    return ORC_OK;
+}
+
 /* bulk conversions, for the conversion pins */
 void orc_f32_to_bf16_n(const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_bf16(x[i]); }
 void orc_f32_to_f16_n (const float *x, uint16_t *y, size_t n) { for (size_t i = 0; i < n; ++i) y[i] = orc_f32_to_f16(x[i]); }
@@ -499,6 +732,13 @@ void orc_hop_n(const void *a, const void *b, void *y, size_t n, int dtype)
 {
     memcpy(y, b, n * orc_esize(dtype));
     hop_run(y, a, n, dtype);
+}
+
+/* y[i] = hop with operator `op` of (a[i], b[i]) */
+void orc_hop_op_n(const void *a, const void *b, void *y, size_t n, int dtype, int op)
+{
+    memcpy(y, b, n * orc_esize(dtype));
+    hop_run_op(y, a, n, dtype, op);
 }
 
 /* thread control for the timing harness: 0 = leave the OpenMP default */

@@ -16,6 +16,9 @@ import numpy as np
 
 FP32, BF16, FP16, INT32 = 0, 1, 2, 3
 PHASE_RS, PHASE_AG = 0, 1
+SUM, PROD, MAX, MIN = 0, 1, 2, 3
+ORDER_RING, ORDER_TREE = 0, 1
+ROUND_EACH, ROUND_ONCE = 0, 1
 NP_WIRE = {FP32: np.float32, BF16: np.uint16, FP16: np.uint16, INT32: np.int32}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -55,6 +58,14 @@ def lib():
         L.orc_allreduce_fp32acc.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip]
         L.orc_reduce_scatter_fp32acc.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip]
         L.orc_reduce_fp32acc.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ip, ctypes.c_int]
+        L.orc_allreduce_op.argtypes = [vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ip, ctypes.c_size_t]
+        L.orc_reduce_scatter_op.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ip, ctypes.c_size_t]
+        L.orc_reduce_op.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ip, ctypes.c_int, ctypes.c_size_t]
+        L.orc_allreduce_var.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ip, ctypes.c_int, ctypes.c_int]
+        L.orc_reduce_scatter_var.argtypes = L.orc_allreduce_var.argtypes
+        L.orc_reduce_var.argtypes = [vpp, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.orc_hop_op_n.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int]
+        L.orc_hop_op_n.restype = None
         L.orc_set_threads.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
@@ -96,14 +107,17 @@ def ring_step(W, ring, phase, step, rank):
     return sb.value, rb.value
 
 
-def allreduce(inputs, dtype, ring=None, chunk_elems=0):
-    """Ring All-Reduce (sum).  inputs: W arrays of `count` wire elements.
+def allreduce(inputs, dtype, ring=None, chunk_elems=0, op=SUM):
+    """Ring All-Reduce with operator `op`.  inputs: W arrays of `count` wire elements.
     Returns W new arrays; the inputs are left untouched."""
     W = len(inputs)
     work = [_wire(a, dtype).copy() for a in inputs]
     count = work[0].size
     assert all(w.size == count for w in work)
-    _check(lib().orc_allreduce(_ptrs(work), W, count, dtype, _ring_arg(ring, W), chunk_elems), "allreduce")
+    if op == SUM:
+        _check(lib().orc_allreduce(_ptrs(work), W, count, dtype, _ring_arg(ring, W), chunk_elems), "allreduce")
+    else:
+        _check(lib().orc_allreduce_op(_ptrs(work), W, count, dtype, op, _ring_arg(ring, W), chunk_elems), "allreduce_op")
     return work
 
 
@@ -117,8 +131,8 @@ def allreduce_inplace(work, dtype, ring=None, chunk_elems=0):
     return work
 
 
-def reduce_scatter(inputs, dtype, ring=None, chunk_elems=0):
-    """Ring Reduce-Scatter (sum).  inputs: W arrays of W*recvcount elements.
+def reduce_scatter(inputs, dtype, ring=None, chunk_elems=0, op=SUM):
+    """Ring Reduce-Scatter with operator `op`.  inputs: W arrays of W*recvcount elements.
     Returns W arrays of recvcount elements (rank r gets block r)."""
     W = len(inputs)
     work = [_wire(a, dtype).copy() for a in inputs]
@@ -126,8 +140,12 @@ def reduce_scatter(inputs, dtype, ring=None, chunk_elems=0):
     assert total % W == 0 and all(w.size == total for w in work)
     n = total // W
     out = [np.empty(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
-    _check(lib().orc_reduce_scatter(_ptrs(work), _ptrs(out), W, n, dtype, _ring_arg(ring, W), chunk_elems),
-           "reduce_scatter")
+    if op == SUM:
+        _check(lib().orc_reduce_scatter(_ptrs(work), _ptrs(out), W, n, dtype, _ring_arg(ring, W), chunk_elems),
+               "reduce_scatter")
+    else:
+        _check(lib().orc_reduce_scatter_op(_ptrs(work), _ptrs(out), W, n, dtype, op, _ring_arg(ring, W), chunk_elems),
+               "reduce_scatter_op")
     return out
 
 
@@ -144,14 +162,18 @@ def all_gather(inputs, dtype, ring=None, chunk_elems=0):
     return out
 
 
-def reduce(inputs, dtype, root, ring=None, chunk_elems=0):
-    """Ring Reduce (sum) to `root`.  inputs: W arrays of count elements.  Returns the root's result."""
+def reduce(inputs, dtype, root, ring=None, chunk_elems=0, op=SUM):
+    """Ring Reduce with operator `op` to `root`.  inputs: W arrays of count elements.  Returns the root's result."""
     W = len(inputs)
     src = [_wire(a, dtype) for a in inputs]
     n = src[0].size
     assert all(s.size == n for s in src)
     out = np.zeros(n, dtype=NP_WIRE[dtype])
-    _check(lib().orc_reduce(_ptrs(src), out.ctypes.data, W, n, dtype, _ring_arg(ring, W), root, chunk_elems), "reduce")
+    if op == SUM:
+        _check(lib().orc_reduce(_ptrs(src), out.ctypes.data, W, n, dtype, _ring_arg(ring, W), root, chunk_elems), "reduce")
+    else:
+        _check(lib().orc_reduce_op(_ptrs(src), out.ctypes.data, W, n, dtype, op, _ring_arg(ring, W), root, chunk_elems),
+               "reduce_op")
     return out
 
 
@@ -202,6 +224,47 @@ def reduce_fp32acc(inputs, dtype, root, ring=None):
     _check(lib().orc_reduce_fp32acc(_ptrs(src), out.ctypes.data, W, src[0].size, dtype, _ring_arg(ring, W), root),
            "reduce_fp32acc")
     return out
+
+
+def allreduce_var(inputs, dtype, op=SUM, ring=None, order=ORDER_RING, rounding=ROUND_EACH):
+    """All-Reduce variant: operator, order (ring / tree) and rounding (every
+    intermediate result / once at the end) chosen freely.  (RING, EACH) is the ring itself."""
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    n = src[0].size
+    out = [np.zeros(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_allreduce_var(_ptrs(src), _ptrs(out), W, n, dtype, op, _ring_arg(ring, W), order, rounding),
+           "allreduce_var")
+    return out
+
+
+def reduce_scatter_var(inputs, dtype, op=SUM, ring=None, order=ORDER_RING, rounding=ROUND_EACH):
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    total = src[0].size
+    assert total % W == 0
+    out = [np.zeros(total // W, dtype=NP_WIRE[dtype]) for _ in range(W)]
+    _check(lib().orc_reduce_scatter_var(_ptrs(src), _ptrs(out), W, total // W, dtype, op, _ring_arg(ring, W),
+                                        order, rounding), "reduce_scatter_var")
+    return out
+
+
+def reduce_var(inputs, dtype, root, op=SUM, ring=None, order=ORDER_RING, rounding=ROUND_EACH):
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    out = np.zeros(src[0].size, dtype=NP_WIRE[dtype])
+    _check(lib().orc_reduce_var(_ptrs(src), out.ctypes.data, W, src[0].size, dtype, op, _ring_arg(ring, W), root,
+                                order, rounding), "reduce_var")
+    return out
+
+
+def hop_op(incoming, local, dtype, op):
+    """Element-wise single hop with operator `op`."""
+    a, b = _wire(incoming, dtype), _wire(local, dtype)
+    assert a.size == b.size
+    y = np.empty_like(a)
+    lib().orc_hop_op_n(a.ctypes.data, b.ctypes.data, y.ctypes.data, a.size, dtype, op)
+    return y
 
 
 def hop(incoming, local, dtype):

@@ -177,3 +177,130 @@ def allreduce_fp32acc(inputs, fmt, ring=None):
         for i in range(lo, hi):
             out[i] = sum_fp32acc([inputs[r][i] for r in order], fmt)
     return out
+
+
+# ---------------------------------------------------------------------------
+# other operators, the tree order, rounding once: exact arithmetic as above
+# ---------------------------------------------------------------------------
+def _special(fmt, kind, sign=0):
+    eb, fb = FMT[fmt]
+    top = ((1 << eb) - 1) << fb
+    if kind == "nan":
+        return top | (1 << (fb - 1))
+    return (sign << (eb + fb)) | top
+
+
+def mul_round(a_bits, b_bits, src_fmt, dst_fmt):
+    """round_dst(a * b) with IEEE rules for specials: 0 * inf = NaN, sign = xor of the signs."""
+    a, b = decode(a_bits, src_fmt), decode(b_bits, src_fmt)
+    if a[0] == "nan" or b[0] == "nan":
+        return _special(dst_fmt, "nan")
+    sa = a[1] if a[0] == "inf" else a[2]
+    sb = b[1] if b[0] == "inf" else b[2]
+    sign = sa ^ sb
+    if a[0] == "inf" or b[0] == "inf":
+        other = b if a[0] == "inf" else a
+        if other[0] == "num" and other[1] == 0:
+            return _special(dst_fmt, "nan")
+        return _special(dst_fmt, "inf", sign)
+    return encode(a[1] * b[1], sign, dst_fmt)
+
+
+def pick_extreme(a_bits, b_bits, fmt, want_max):
+    """maximum / minimum of IEEE 754-2019 (clause 9.6): NaN if either is NaN; -0 < +0."""
+    a, b = decode(a_bits, fmt), decode(b_bits, fmt)
+    if a[0] == "nan" or b[0] == "nan":
+        return _special(fmt, "nan")
+
+    def key(d):     # (value as a comparable, sign of zero as tie break): larger key = larger number
+        if d[0] == "inf":
+            return (2, 0, 0) if d[1] == 0 else (-2, 0, 0)
+        return (0, d[1], -d[2])
+
+    ka, kb = key(a), key(b)
+    if ka == kb:
+        return a_bits
+    a_larger = ka > kb
+    return a_bits if (a_larger == want_max) else b_bits
+
+
+def node(a_bits, b_bits, fmt, op):
+    """One hop / tree node with per-result rounding to fmt; operands and result are fmt bit patterns."""
+    if op == "sum":
+        return hop(a_bits, b_bits, fmt)
+    if op == "prod":
+        p32 = mul_round(widen(a_bits, fmt), widen(b_bits, fmt), "fp32", "fp32")
+        d = decode(p32, "fp32")
+        if d[0] == "nan":
+            return _special(fmt, "nan")
+        if d[0] == "inf":
+            return _special(fmt, "inf", d[1])
+        return encode(d[1], d[2], fmt)
+    return pick_extreme(a_bits, b_bits, fmt, op == "max")
+
+
+def node_int32(a, b, op):
+    if op == "sum":
+        return hop_int32(a, b)
+    if op == "prod":
+        s = (a * b) & 0xFFFFFFFF
+        return s - (1 << 32) if s >= (1 << 31) else s
+    return max(a, b) if op == "max" else min(a, b)
+
+
+def node32(a32, b32, op):
+    """The same on binary32 bit patterns without narrowing (for rounding once)."""
+    if op == "sum":
+        return add_round(a32, b32, "fp32", "fp32")
+    if op == "prod":
+        return mul_round(a32, b32, "fp32", "fp32")
+    return pick_extreme(a32, b32, "fp32", op == "max")
+
+
+def narrow(x32, fmt):
+    d = decode(x32, "fp32")
+    if d[0] == "nan":
+        return _special(fmt, "nan")
+    if d[0] == "inf":
+        return _special(fmt, "inf", d[1])
+    return encode(d[1], d[2], fmt)
+
+
+def combine(vals, fmt, op="sum", order="ring", rounding="each"):
+    """vals: wire bit patterns (ints for int32) in the order they enter.  Ring: left fold.
+    Tree: neighbours first, level by level, an odd last value moves up unchanged."""
+    if fmt == "int32":
+        f = lambda a, b: node_int32(a, b, op)
+    elif rounding == "each":
+        f = lambda a, b: node(a, b, fmt, op)
+    else:
+        vals = [widen(v, fmt) for v in vals]
+        f = lambda a, b: node32(a, b, op)
+    vals = list(vals)
+    if order == "ring":
+        acc = vals[0]
+        for v in vals[1:]:
+            acc = f(acc, v)
+    else:
+        while len(vals) > 1:
+            nxt = [f(vals[k], vals[k + 1]) for k in range(0, len(vals) - 1, 2)]
+            if len(vals) & 1:
+                nxt.append(vals[-1])
+            vals = nxt
+        acc = vals[0]
+    if fmt != "int32" and rounding != "each":
+        acc = narrow(acc, fmt)
+    return acc
+
+
+def allreduce_var(inputs, fmt, op="sum", ring=None, order="ring", rounding="each"):
+    """What every rank must hold after the All-Reduce variant."""
+    W = len(inputs)
+    count = len(inputs[0])
+    ring = list(range(W)) if ring is None else list(ring)
+    out = [None] * count
+    for c, (lo, hi) in enumerate(block_ranges(count, W)):
+        who = fold_order(c, ring) if order == "ring" else ring
+        for i in range(lo, hi):
+            out[i] = combine([inputs[r][i] for r in who], fmt, op, order, rounding)
+    return out
