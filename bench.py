@@ -36,7 +36,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X datasheet, HBM3E
-KERNEL_SOURCES = ["paper_2601_22585_amd/csrc/reduce_copy.hip", "paper_2601_22585_amd/csrc/reduce_copy.h"]
+KERNEL_SOURCES = ["paper_2601_22585_amd/csrc/reduce_copy.hip", "paper_2601_22585_amd/csrc/ring_fused.hip",
+                  "paper_2601_22585_amd/csrc/wire.h", "paper_2601_22585_amd/csrc/reduce_copy.h"]
 
 
 def kernel_source_hash():
@@ -75,6 +76,10 @@ def parse():
     ap.add_argument("--fuse-rs-ag", action="store_true")
     ap.add_argument("--accumulate", default="per_hop", choices=["per_hop", "fp32"],
                     help="fp32: fused sums with binary32 accumulation and one rounding (a reordered-class result)")
+    ap.add_argument("--reduce-op", default="sum", choices=["sum", "prod", "max", "min"],
+                    help="reduction operator of the reducing collectives")
+    ap.add_argument("--order", default="ring", choices=["ring", "tree"],
+                    help="tree: fused reductions over a neighbours-first tree (a reordered-class result)")
     ap.add_argument("--inplace", action="store_true")
     ap.add_argument("--bytes-per-rank", type=int, default=0, help="config 3: bytes per rank buffer")
     ap.add_argument("--shard-elems", type=int, default=0, help="config 4: elements per shard (default 2 GiB worth)")
@@ -153,6 +158,12 @@ def main():
                nontemporal=args.nontemporal)
     if args.accumulate != "per_hop":
         opt["accumulate"] = args.accumulate
+    if args.order != "ring":
+        opt["order"] = args.order
+    reducing = op in ("allreduce", "reduce_scatter", "reduce")
+    if args.reduce_op != "sum":
+        assert reducing, "--reduce-op applies to allreduce, reduce_scatter and reduce"
+        opt["op"] = args.reduce_op
     if op == "allreduce":
         opt["fuse_rs_ag"] = args.fuse_rs_ag
         send = [new(count) for _ in range(W)]
@@ -225,11 +236,17 @@ def main():
         else:
             ins = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in win]) for r in range(W)]
         wide = args.accumulate == "fp32"
-        fn = {"allreduce": (lambda a, c_, chunk_elems=0: orc.allreduce_fp32acc(a, c_)) if wide else orc.allreduce,
-              "reduce_scatter": (lambda a, c_, chunk_elems=0: orc.reduce_scatter_fp32acc(a, c_)) if wide else orc.reduce_scatter,
+        oop = {"sum": orc.SUM, "prod": orc.PROD, "max": orc.MAX, "min": orc.MIN}[args.reduce_op]
+        variant = wide or args.order == "tree"      # the closed-form replay; otherwise the ring as message passing
+        vkw = dict(op=oop, order=orc.ORDER_TREE if args.order == "tree" else orc.ORDER_RING,
+                   rounding=orc.ROUND_ONCE if wide else orc.ROUND_EACH)
+        fn = {"allreduce": (lambda a, c_, chunk_elems=0: orc.allreduce_var(a, c_, **vkw)) if variant
+                           else (lambda a, c_, chunk_elems=0: orc.allreduce(a, c_, chunk_elems=chunk_elems, op=oop)),
+              "reduce_scatter": (lambda a, c_, chunk_elems=0: orc.reduce_scatter_var(a, c_, **vkw)) if variant
+                                else (lambda a, c_, chunk_elems=0: orc.reduce_scatter(a, c_, chunk_elems=chunk_elems, op=oop)),
               "all_gather": orc.all_gather,
-              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce_fp32acc(a, c_, 0) if wide
-                                                      else orc.reduce(a, c_, 0, chunk_elems=chunk_elems)],
+              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce_var(a, c_, 0, **vkw) if variant
+                                                      else orc.reduce(a, c_, 0, chunk_elems=chunk_elems, op=oop)],
               "broadcast": lambda a, c_, chunk_elems=0: orc.broadcast(a[0], c_, W, 0),
               "alltoall": lambda a, c_, chunk_elems=0: orc.alltoall(a, c_)}[op]
         # one thread first, on an eighth of the sample, then every host core on all of it
@@ -322,7 +339,9 @@ def main():
         bytes_per_launch = call_bytes / launches
         n_dom, dom, units = launches, list(range(launches)), float(launches)
     elif args.sched == "fused":
-        kernel = f"ring_fused_vec<{dtype},W={W}>" if op in ("allreduce", "reduce_scatter", "reduce") else "gather_fused_vec"
+        general = args.reduce_op != "sum" or args.order == "tree"
+        kernel = ((f"ring_fused_gen<{dtype},W={W}>" if general else f"ring_fused_vec<{dtype},W={W}>")
+                  if reducing else "gather_fused_vec")
         call_bytes = 2 * W * S if op == "allreduce" else (W + 1) * S
         bytes_per_launch, n_dom, dom, units = call_bytes, 1, [0], 1.0
     elif op == "broadcast":
@@ -393,7 +412,8 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
                    "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
-                   "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph), "accumulate": args.accumulate},
+                   "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph), "accumulate": args.accumulate,
+                   "reduce_op": args.reduce_op if reducing else None, "order": args.order},
         "algbw_rank_equiv_GBps": round(W * value, 2),
         "call_hbm_GBps": round(call_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "call_hbm_frac_of_peak": round(call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

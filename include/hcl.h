@@ -61,19 +61,26 @@ extern "C" {
 #endif
 
 #define HCL_MAX_RANKS 16
-#define HCL_VERSION 100
+#define HCL_VERSION 101
 
 typedef enum {
   HCL_OK = 0,
   HCL_ERR_INVALID_ARG = 1, /* null pointer, W out of range, bad ring, misaligned pointer or chunk */
-  HCL_ERR_UNSUPPORTED = 2, /* op other than sum, unknown dtype / schedule / transport combination */
+  HCL_ERR_UNSUPPORTED = 2, /* unknown operator / dtype, or a schedule / transport / order combination
+                              that does not exist */
   HCL_ERR_ALIAS = 3,       /* buffers overlap in a way the schedule cannot honour */
   HCL_ERR_WORKSPACE = 4,   /* opts->workspace or opts->host_stage missing or too small */
   HCL_ERR_HIP = 5          /* a HIP runtime call failed */
 } hcl_status_t;
 
 typedef enum { HCL_FP32 = 0, HCL_BF16 = 1, HCL_FP16 = 2, HCL_INT32 = 3 } hcl_dtype_t;
-typedef enum { HCL_SUM = 0 } hcl_op_t;
+/* Reduction operator of one hop: partial = round_T(op(f32(incoming), f32(local))).
+ * SUM and PROD round to nearest even (the product of two bf16 / fp16 values is
+ * exact in binary32, so PROD is the correctly rounded product); MAX and MIN
+ * return one of the operands and follow IEEE 754-2019 `maximum` / `minimum`: a
+ * NaN operand gives NaN, -0 orders below +0.  int32: SUM and PROD wrap modulo
+ * 2^32, MAX and MIN compare as signed integers. */
+typedef enum { HCL_SUM = 0, HCL_PROD = 1, HCL_MAX = 2, HCL_MIN = 3 } hcl_op_t;
 
 /* STEPWISE: the ring as each rank executes it, one launch per ring step doing
  *   every rank's reduce-copy (or copy) of that step.
@@ -97,6 +104,17 @@ typedef enum { HCL_XPORT_DIRECT = 0, HCL_XPORT_HOST_STAGED = 1 } hcl_xport_t;
  *   paper tolerates between backends (Appendix E.2) -- within 2 ulp of the
  *   correctly rounded exact sum; for fp32 and int32 it is the ring's result. */
 typedef enum { HCL_ACC_PER_HOP = 0, HCL_ACC_FP32 = 1 } hcl_acc_t;
+
+/* RING: block c's values enter its reduction in the order next(c), ..., c -- the
+ *   order the stepwise ring produces.
+ * TREE (FUSED reductions only): the ranks' values are taken in ring order
+ *   ring[0], ..., ring[W-1], the same for every block, and combined level by
+ *   level, neighbours first ((v0 op v1), (v2 op v3), ...; an odd last value moves
+ *   up unchanged).  A reordered-class result (Appendix E.2): different bits from
+ *   the ring's for the float types' SUM and PROD, identical for MAX, MIN and int32.
+ *   With PER_HOP every node is rounded to the wire type, with HCL_ACC_FP32 the
+ *   tree is evaluated in binary32 and rounded once. */
+typedef enum { HCL_ORDER_RING = 0, HCL_ORDER_TREE = 1 } hcl_order_t;
 
 typedef enum {
   HCL_KIND_ALLREDUCE = 0, HCL_KIND_REDUCE_SCATTER = 1, HCL_KIND_ALL_GATHER = 2,
@@ -133,6 +151,7 @@ typedef struct hcl_opts {
                               after the last launch: the cheap way to time a phase's launches   */
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
   int accumulate;          /* hcl_acc_t; anything but PER_HOP needs sched == FUSED           */
+  int order;               /* hcl_order_t; TREE needs sched == FUSED                          */
 } hcl_opts_t;
 
 /* One unit of the ring schedule, as hcl_schedule_items reports it. */

@@ -7,11 +7,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhcl.so")
-SOURCES = ["hcl_api.cpp", "reduce_copy.hip"]
-HEADERS = ["reduce_copy.h", "ring_sched.h"]
+SOURCES = ["hcl_api.cpp", "reduce_copy.hip", "ring_fused.hip"]   # ring_fused.hip is compiled once per wire type and part
+HEADERS = ["reduce_copy.h", "ring_sched.h", "wire.h"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -32,11 +32,37 @@ def build_lib(force=True, verbose=False):
     if not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    # translation units: the API, the step kernels, and the fused kernels once per
+    # (wire type, part) -- compiled side by side, then one link
+    units = [("hcl_api.cpp", "hcl_api", []), ("reduce_copy.hip", "reduce_copy", [])]
+    for dt in range(4):
+        for part in range(2):
+            units.append(("ring_fused.hip", f"ring_fused_dt{dt}_p{part}", [f"-DHCL_FUSED_DT={dt}", f"-DHCL_FUSED_PART={part}"]))
+    objs, cmds = [], []
+    for src, name, defs in units:
+        obj = os.path.join(objdir, name + ".o")
+        cmds.append([hipcc, *HIPCC_FLAGS, *defs, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+                     "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
+    jobs = max(1, min(len(cmds), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1))))
+    running, pending = [], list(cmds)
+    while pending or running:
+        while pending and len(running) < jobs:
+            cmd = pending.pop(0)
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            running.append((cmd, subprocess.Popen(cmd)))
+        cmd, p = running.pop(0)
+        if p.wait() != 0:
+            for _, q in running:
+                q.kill()
+            raise subprocess.CalledProcessError(p.returncode, cmd)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+        print(" ".join(link), flush=True)
+    subprocess.check_call(link)
     return LIB
 
 

@@ -201,6 +201,9 @@ struct Ctx {
   uint64_t es = 4;
   uint64_t chunk_elems = 0;  // 0 = one chunk per block
   int sched = 0, xport = 0;
+  int op = 0;         // hcl_op_t of the reducing collectives
+  bool tree = false;  // FUSED: tree order instead of ring order
+  bool wide = false;  // FUSED: binary32 intermediates, one rounding
   bool fuse_rs_ag = false;
   Tuning tune{};
   int max_blocks = 0;
@@ -210,9 +213,11 @@ struct Ctx {
   bool phase_events = false;  // events at phase boundaries instead of around every launch
   int phases = 0;
 
-  hcl_status_t init(int W_, hcl_dtype_t dt, size_t chunk_bytes, const hcl_opts_t* o, void* st) {
+  hcl_status_t init(int W_, hcl_dtype_t dt, size_t chunk_bytes, const hcl_opts_t* o, void* st, int op_ = HCL_SUM) {
     opts = o;
     stream = st;
+    if (op_ < HCL_SUM || op_ > HCL_MIN) return fail(HCL_ERR_UNSUPPORTED, "unknown reduction operator %d", op_);
+    op = op_;
     if (W_ < 1 || W_ > kMaxRanks) return fail(HCL_ERR_INVALID_ARG, "W = %d outside [1,%d]", W_, kMaxRanks);
     if (!ring.init(W_, o ? o->ring : nullptr)) return fail(HCL_ERR_INVALID_ARG, "ring is not a permutation of 0..W-1");
     W = W_;
@@ -232,7 +237,12 @@ struct Ctx {
     if (acc != HCL_ACC_PER_HOP && acc != HCL_ACC_FP32) return fail(HCL_ERR_UNSUPPORTED, "unknown accumulate mode %d", acc);
     if (acc == HCL_ACC_FP32 && sched != HCL_SCHED_FUSED)
       return fail(HCL_ERR_UNSUPPORTED, "binary32 accumulation exists for the fused schedule only: in a stepwise ring the partial travels in the wire type");
-    tune.wide_acc = acc == HCL_ACC_FP32;
+    wide = acc == HCL_ACC_FP32;
+    const int order = o ? o->order : 0;
+    if (order != HCL_ORDER_RING && order != HCL_ORDER_TREE) return fail(HCL_ERR_UNSUPPORTED, "unknown order %d", order);
+    if (order == HCL_ORDER_TREE && sched != HCL_SCHED_FUSED)
+      return fail(HCL_ERR_UNSUPPORTED, "tree order exists for the fused schedule only: a stepwise ring adds in ring order");
+    tree = order == HCL_ORDER_TREE;
     if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
     if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
     phase_events = o && o->events_per_phase;
@@ -314,6 +324,7 @@ struct Ctx {
     a.tiles_per_chunk = (uint32_t)tpc;
     a.total_tiles = (uint32_t)total;
     a.stagger = stagger_for(tpc);
+    a.op = nsrc == 2 ? (uint32_t)op : 0u;
     t.blocks = grid_for(a.total_tiles);
     hcl_status_t st = mark(launches);
     if (st) return st;
@@ -336,6 +347,8 @@ struct Ctx {
     Tuning t = tune;
     t.vec = al;
     t.unroll = copy_mode ? 4 : fused_unroll(W);
+    // the general-form kernel (operator other than the sum, or tree order) is built for small workgroups
+    if (!copy_mode && al && (op != HCL_SUM || tree) && t.threads > kGenMaxThreads) t.threads = kGenMaxThreads;
     const uint64_t tile = tile_elems(dtype, t);
     const uint64_t tpc = ceil_div(chunk, tile);
     const uint64_t total = nchunks * (uint64_t)(one_block ? 1 : W) * tpc;
@@ -343,6 +356,9 @@ struct Ctx {
     a.chunk = chunk;
     a.tiles_per_chunk = (uint32_t)tpc;
     a.total_tiles = (uint32_t)total;
+    a.op = copy_mode ? 0 : (uint8_t)op;
+    a.tree = !copy_mode && tree;
+    a.wide = !copy_mode && wide;
     t.blocks = grid_for(a.total_tiles);
     hcl_status_t st = mark(launches);
     if (st) return st;
@@ -598,9 +614,8 @@ extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* 
                                           hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
                                           const hcl_opts_t* opts, void* stream) {
   Ctx c;
-  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream, op);
   if (st) return st;
-  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
   if (size_overflows(count, 1, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
   if (count == 0) return c.finish();
   if ((st = check_ptrs(send, recv, W, c.es))) return st;
@@ -648,9 +663,8 @@ extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* co
                                                hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
                                                const hcl_opts_t* opts, void* stream) {
   Ctx c;
-  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream, op);
   if (st) return st;
-  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
   if (size_overflows(recvcount, (uint64_t)W, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");
   if (recvcount == 0) return c.finish();
   if ((st = check_ptrs(send, recv, W, c.es))) return st;
@@ -766,9 +780,8 @@ extern "C" hcl_status_t hcl_reduce_sim(const void* const* send, void* const* rec
                                        hcl_dtype_t dtype, hcl_op_t op, int root, size_t chunk_bytes,
                                        const hcl_opts_t* opts, void* stream) {
   Ctx c;
-  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream);
+  hcl_status_t st = c.init(W, dtype, chunk_bytes, opts, stream, op);
   if (st) return st;
-  if (op != HCL_SUM) return fail(HCL_ERR_UNSUPPORTED, "only the sum reduction is implemented");
   if ((st = only_direct(c, "Reduce"))) return st;
   if (root < 0 || root >= W) return fail(HCL_ERR_INVALID_ARG, "root %d out of range", root);
   if (size_overflows(count, 1, c.es)) return fail(HCL_ERR_INVALID_ARG, "count overflows");

@@ -6,6 +6,7 @@
 namespace hcl {
 
 constexpr int kMaxSegs = 32;
+constexpr int kMaxFusedRanks = 16;
 
 // One rank's work in one ring step: dst0[i] (and dst1[i]) = hop(src0[i], src1[i])
 // for NSRC = 2, or = src0[i] for NSRC = 1, i in [0, n).
@@ -26,6 +27,8 @@ struct StepArgs {
   uint32_t total_tiles;
   uint32_t stagger;  // segment d starts its walk through a chunk d * stagger tiles in (mod tiles_per_chunk)
   uint64_t chunk;    // elements per chunk (> 0)
+  uint32_t op;       // NSRC = 2: 0 sum, 1 product, 2 maximum, 3 minimum
+  uint32_t pad_;
 };
 
 // Whole-collective launch: every element's ring pass stays in one thread.
@@ -42,7 +45,10 @@ struct FusedArgs {
   uint32_t W;
   uint32_t mode;        // 0 All-Reduce, 1 Reduce-Scatter, 2 All-Gather, 3 Reduce, 4 Broadcast
   uint32_t root;        // Reduce / Broadcast: the whole vector is one block that belongs to this rank
-  uint32_t pad_;
+  uint8_t op;           // 0 sum, 1 product, 2 maximum, 3 minimum
+  uint8_t tree;         // 0: ring order, block c's values enter as next(c) .. c; 1: tree over ring order
+  uint8_t wide;         // 1: binary32 intermediates, one rounding at the end (two-byte float types)
+  uint8_t pad_;
 };
 
 struct Tuning {
@@ -51,16 +57,24 @@ struct Tuning {
   int unroll;       // 1, 2, 4, 8
   bool nontemporal;
   bool vec;         // 128-bit path allowed (all addresses 16-byte aligned)
-  bool wide_acc;    // fused sums: binary32 accumulation, one final rounding (two-byte float types)
 };
 
 // Elements one tile covers for this dtype / tuning (vector path or not, same figure).
 uint64_t tile_elems(int dtype, const Tuning& t);
-// Unroll the fused kernel uses for a given W (fixed per W at compile time).
-int fused_unroll(int W);
+// 128-bit vectors per thread and source the fused kernels keep in flight for a given W.
+constexpr int fused_unroll(int W) { return W <= 4 ? 4 : (W <= 8 ? 2 : 1); }
+
+// The general-form fused kernel keeps every rank's vector and its widened
+// elements in registers: it is built for workgroups of at most this many threads.
+constexpr int kGenMaxThreads = 256;
 
 // Both return a hipError_t value (0 = success) from the launch.
 int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& t, void* stream);
 int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream);
+
+// Per wire type (0 fp32, 1 bf16, 2 fp16, 3 int32), one object file each:
+// ring-order sums, copies and the element-wise path / the general form.
+template <int DT> int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream);
+template <int DT> int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream);
 
 }  // namespace hcl

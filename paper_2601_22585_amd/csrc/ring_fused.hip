@@ -1,0 +1,424 @@
+// gfx950 kernels for the FUSED schedule: the whole ring pass of an element
+// stays inside one thread, every rank's value is read once.
+//
+// This file is compiled once per (HCL_FUSED_DT, HCL_FUSED_PART): the wire type
+// (0 fp32, 1 bf16, 2 fp16, 3 int32) and the part -- 0: ring-order sums, the
+// All-Gather / Broadcast kernel and the element-wise path; 1: the general form
+// (run-time operator, tree order, rounding once).  Each object file holds one
+// explicit instantiation of launch_fused_sum<DT> or launch_fused_gen<DT>.
+#include "wire.h"
+
+#if !defined(HCL_FUSED_DT) || !defined(HCL_FUSED_PART)
+#error "compile with -DHCL_FUSED_DT=<0..3> -DHCL_FUSED_PART=<0|1>"
+#endif
+
+namespace hcl {
+
+
+#if HCL_FUSED_PART == 0
+// ---------------------------------------------------------------------------
+// FUSED: the whole ring pass of an element inside one thread.
+// Block c's sum starts at the rank after c in the ring and ends at c, rounding
+// to the wire type after every addition -- the value the stepwise ring
+// produces, with each rank's element read once.
+// ---------------------------------------------------------------------------
+
+template <int DT, int W, bool NT, bool WIDE>
+__global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
+  typedef typename Wire<DT>::elem_t elem_t;
+  constexpr uint32_t ES = sizeof(elem_t);
+  constexpr uint32_t VE = 16 / ES;
+  constexpr int U = fused_unroll(W);
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+  const uint32_t tile = nthr * VE * U;
+  const bool to_all = a.mode == 0;
+  const bool whole = a.mode == 3;  // Reduce: one block, the whole vector, summed in the root's order
+
+  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : (uint32_t)W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
+    if (blo > a.count) blo = a.count;
+    if (bhi > a.count) bhi = a.count;
+    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
+    if (len == 0) continue;
+
+    const uint64_t voff = (blo + p.lo) * ES;  // offset inside a full vector
+    const uint32_t pc = a.pos[c];
+    const char* sp[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(pc + 1 + k) % W]] + voff;
+
+    const uint32_t nvec = len / VE;
+    u32x4 v[U][W];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t vi = u * nthr + tid;
+      if (vi < nvec) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) v[u][k] = ld16<NT>(sp[k] + vi * 16u);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t vi = u * nthr + tid;
+      if (vi < nvec) {
+        u32x4 acc;
+        if (WIDE) {
+          acc = sum_wide<DT, W>(v[u]);
+        } else {
+          acc = v[u][0];
+#pragma unroll
+          for (int k = 1; k < W; ++k) acc = hop_vec<DT>(acc, v[u][k]);
+        }
+        if (to_all) {
+#pragma unroll
+          for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
+        } else {
+          st16<NT>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+        }
+      }
+    }
+    const uint32_t e = nvec * VE + tid;
+    if (e < len) {
+      elem_t acc = reinterpret_cast<const elem_t*>(sp[0])[e];
+      if (WIDE) {
+        float f = widen1<DT>(acc);
+#pragma unroll
+        for (int k = 1; k < W; ++k) f = f + widen1<DT>(reinterpret_cast<const elem_t*>(sp[k])[e]);
+        acc = narrow1<DT>(f);
+      } else {
+#pragma unroll
+        for (int k = 1; k < W; ++k) acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(sp[k])[e]);
+      }
+      if (to_all) {
+#pragma unroll
+        for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
+      } else {
+        reinterpret_cast<elem_t*>(a.dst[c] + p.lo * ES)[e] = acc;
+      }
+    }
+  }
+}
+
+// All-Gather in one launch: block c is read once from rank c and stored to all ranks.
+template <int ES, bool NT>
+__global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
+  constexpr uint32_t VE = 16 / ES;
+  constexpr int U = 4;
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+  const uint32_t tile = nthr * VE * U;
+  const uint32_t W = a.W;
+  const bool whole = a.mode == 4;  // Broadcast: one block, the root's whole vector
+  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    const uint32_t len = tile_len(p, a.B, a.chunk, tile);
+    if (len == 0) continue;
+    const char* s = a.src[c] + p.lo * ES;
+    const uint64_t voff = ((whole ? 0 : (uint64_t)c * a.B) + p.lo) * ES;
+    const uint32_t nvec = len / VE;
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t vi = u * nthr + tid;
+      if (vi < nvec) v[u] = ld16<NT>(s + vi * 16u);
+    }
+    for (uint32_t r = 0; r < W; ++r) {
+      char* d = a.dst[r] + voff;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t vi = u * nthr + tid;
+        if (vi < nvec) st16<NT>(d + vi * 16u, v[u]);
+      }
+    }
+    const uint32_t e = nvec * VE + tid;
+    if (e < len) {
+      if (ES == 2) {
+        const uint16_t x = reinterpret_cast<const uint16_t*>(s)[e];
+        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint16_t*>(a.dst[r] + voff)[e] = x;
+      } else {
+        const uint32_t x = reinterpret_cast<const uint32_t*>(s)[e];
+        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint32_t*>(a.dst[r] + voff)[e] = x;
+      }
+    }
+  }
+}
+
+// Element-wise fused path (any alignment, any W, every mode, operator, order and rounding).
+template <int DT>
+__global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const uint32_t tile) {
+  typedef typename Wire<DT>::elem_t elem_t;
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+  const uint32_t W = a.W;
+  const bool whole = a.mode >= 3;  // Reduce / Broadcast: one block, the whole vector, owned by the root
+  const bool one_src = a.mode == 2 || a.mode == 4;
+  const bool one_dst = a.mode == 1 || a.mode == 3;
+  const uint32_t op = a.op;
+  const bool tree = a.tree != 0;
+  const bool wide = Wire<DT>::kWide && a.wide != 0;
+  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
+    if (blo > a.count) blo = a.count;
+    if (bhi > a.count) bhi = a.count;
+    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
+    if (len == 0) continue;
+    const uint32_t first = tree ? 0u : a.pos[c] + 1u;
+    for (uint32_t e = tid; e < len; e += nthr) {
+      const uint64_t i = p.lo + e;  // inside block c
+      elem_t acc;
+      if (one_src) {
+        acc = reinterpret_cast<const elem_t*>(a.src[c])[i];
+      } else if (DT == DT_INT32) {
+        uint32_t v[kMaxFusedRanks];
+        for (uint32_t k = 0; k < W; ++k) v[k] = (uint32_t)reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
+        if (!tree) {
+          for (uint32_t k = 1; k < W; ++k) v[0] = apply_i32(op, v[0], v[k]);
+        } else {
+          for (uint32_t n = W; n > 1; n = (n + 1) / 2) {
+            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = apply_i32(op, v[k], v[k + 1]);
+            if (n & 1) v[n / 2] = v[n - 1];
+          }
+        }
+        acc = (elem_t)v[0];
+      } else {
+        float v[kMaxFusedRanks];
+        for (uint32_t k = 0; k < W; ++k) {
+          const elem_t x = reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
+          v[k] = Wire<DT>::kWide ? widen1<DT>(x) : u2f((uint32_t)x);
+        }
+        // one node: the operator, then (unless wide) a trip through the wire type
+        auto node = [&](float x, float y) {
+          float r = apply_f32(op, x, y);
+          if (Wire<DT>::kWide && !wide) r = widen1<DT>(narrow1<DT>(r));
+          return r;
+        };
+        if (!tree) {
+          for (uint32_t k = 1; k < W; ++k) v[0] = node(v[0], v[k]);
+        } else {
+          for (uint32_t n = W; n > 1; n = (n + 1) / 2) {
+            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = node(v[k], v[k + 1]);
+            if (n & 1) v[n / 2] = v[n - 1];
+          }
+        }
+        acc = Wire<DT>::kWide ? narrow1<DT>(v[0]) : (elem_t)f2u(v[0]);
+      }
+      if (one_dst) {
+        reinterpret_cast<elem_t*>(a.dst[c])[i] = acc;
+      } else {
+        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r])[blo + i] = acc;
+      }
+    }
+  }
+}
+
+#else
+// ---------------------------------------------------------------------------
+// FUSED, general form: run-time operator (a.op), ring or tree order (a.tree),
+// per-result rounding or binary32 intermediates with one rounding (a.wide).
+// Ring order: block c's values enter in the order next(c), ..., c.  Tree order:
+// ranks in ring order ring[0] .. ring[W-1] for every block, neighbours combined
+// first, level by level; an odd last value moves up unchanged.
+// ---------------------------------------------------------------------------
+template <int DT, int W>
+__device__ __forceinline__ uint32_t combine_word(const uint32_t (&w)[W], uint32_t op, bool tree, bool wide) {
+  if (DT == DT_INT32) {
+    uint32_t v[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) v[k] = w[k];
+    if (!tree) {
+#pragma unroll
+      for (int k = 1; k < W; ++k) v[0] = apply_i32(op, v[0], v[k]);
+    } else {
+#pragma unroll
+      for (int n = W; n > 1; n = (n + 1) / 2) {
+#pragma unroll
+        for (int k = 0; k + 1 < n; k += 2) v[k / 2] = apply_i32(op, v[k], v[k + 1]);
+        if (n & 1) v[n / 2] = v[n - 1];
+      }
+    }
+    return v[0];
+  }
+  constexpr bool kTwo = Wire<DT>::kWide;  // two elements per word
+  float lo[W], hi[W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) {
+    if (kTwo) {
+      Wire<DT>::widen2(w[k], lo[k], hi[k]);
+    } else {
+      lo[k] = u2f(w[k]);
+      hi[k] = 0.0f;
+    }
+  }
+  // one node: the operator, then (unless wide) a trip through the wire type
+  auto node = [&](float& alo, float& ahi, float blo, float bhi) {
+    alo = apply_f32(op, alo, blo);
+    if (kTwo) {
+      ahi = apply_f32(op, ahi, bhi);
+      if (!wide) Wire<DT>::widen2(Wire<DT>::narrow2(alo, ahi), alo, ahi);
+    }
+  };
+  if (!tree) {
+#pragma unroll
+    for (int k = 1; k < W; ++k) node(lo[0], hi[0], lo[k], hi[k]);
+  } else {
+#pragma unroll
+    for (int n = W; n > 1; n = (n + 1) / 2) {
+#pragma unroll
+      for (int k = 0; k + 1 < n; k += 2) {
+        float a = lo[k], b = hi[k];
+        node(a, b, lo[k + 1], hi[k + 1]);
+        lo[k / 2] = a;
+        hi[k / 2] = b;
+      }
+      if (n & 1) {
+        lo[n / 2] = lo[n - 1];
+        hi[n / 2] = hi[n - 1];
+      }
+    }
+  }
+  return kTwo ? Wire<DT>::narrow2(lo[0], hi[0]) : f2u(lo[0]);
+}
+
+template <int DT, int W, bool NT>
+__global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs a) {
+  typedef typename Wire<DT>::elem_t elem_t;
+  constexpr uint32_t ES = sizeof(elem_t);
+  constexpr uint32_t VE = 16 / ES;
+  constexpr int U = fused_unroll(W);
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+  const uint32_t tile = nthr * VE * U;
+  const bool to_all = a.mode == 0;
+  const bool whole = a.mode == 3;
+  const uint32_t op = a.op;
+  const bool tree = a.tree != 0, wide = a.wide != 0;
+
+  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : (uint32_t)W, a.chunk, tile);
+    const uint32_t c = whole ? a.root : p.d;
+    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
+    if (blo > a.count) blo = a.count;
+    if (bhi > a.count) bhi = a.count;
+    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
+    if (len == 0) continue;
+
+    const uint64_t voff = (blo + p.lo) * ES;
+    const uint32_t first = tree ? 0u : a.pos[c] + 1u;  // ring position of the first value to enter
+    const char* sp[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(first + k) % W]] + voff;
+
+    const uint32_t nvec = len / VE;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t vi = u * nthr + tid;
+      if (vi < nvec) {
+        u32x4 v[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) v[k] = ld16<NT>(sp[k] + vi * 16u);
+        uint32_t wx[W], wy[W], wz[W], ww[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) {
+          wx[k] = v[k].x;
+          wy[k] = v[k].y;
+          wz[k] = v[k].z;
+          ww[k] = v[k].w;
+        }
+        u32x4 acc;
+        acc.x = combine_word<DT, W>(wx, op, tree, wide);
+        acc.y = combine_word<DT, W>(wy, op, tree, wide);
+        acc.z = combine_word<DT, W>(wz, op, tree, wide);
+        acc.w = combine_word<DT, W>(ww, op, tree, wide);
+        if (to_all) {
+#pragma unroll
+          for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
+        } else {
+          st16<NT>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+        }
+      }
+    }
+    const uint32_t e = nvec * VE + tid;
+    if (e < len) {
+      // one element: put it into the low half of a word and combine words
+      uint32_t w1[W];
+#pragma unroll
+      for (int k = 0; k < W; ++k) w1[k] = (uint32_t)reinterpret_cast<const elem_t*>(sp[k])[e];
+      const elem_t acc = (elem_t)combine_word<DT, W>(w1, op, tree, wide);
+      if (to_all) {
+#pragma unroll
+        for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
+      } else {
+        reinterpret_cast<elem_t*>(a.dst[c] + p.lo * ES)[e] = acc;
+      }
+    }
+  }
+}
+
+#endif
+
+// ---------------------------------------------------------------------------
+// host-side dispatch
+// ---------------------------------------------------------------------------
+#if HCL_FUSED_PART == 0
+template <int DT>
+int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const dim3 g(t.blocks), b(t.threads);
+  if (!t.vec) {
+    const uint32_t es = sizeof(typename Wire<DT>::elem_t);
+    const int U = (a.mode == 2 || a.mode == 4) ? 4 : fused_unroll((int)a.W);
+    ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U));
+    return (int)hipGetLastError();
+  }
+  if (a.mode == 2 || a.mode == 4) {
+    constexpr int ES = sizeof(typename Wire<DT>::elem_t);
+    if (t.nontemporal) gather_fused_vec<ES, true><<<g, b, 0, s>>>(a);
+    else gather_fused_vec<ES, false><<<g, b, 0, s>>>(a);
+    return (int)hipGetLastError();
+  }
+  constexpr bool kW = Wire<DT>::kWide;
+  const bool wide = kW && a.wide;
+#define HCL_CASE(WW)                                                                      \
+  case WW:                                                                                \
+    if (wide) {                                                                           \
+      if (t.nontemporal) ring_fused_vec<DT, WW, true, kW><<<g, b, 0, s>>>(a);             \
+      else ring_fused_vec<DT, WW, false, kW><<<g, b, 0, s>>>(a);                          \
+    } else {                                                                              \
+      if (t.nontemporal) ring_fused_vec<DT, WW, true, false><<<g, b, 0, s>>>(a);          \
+      else ring_fused_vec<DT, WW, false, false><<<g, b, 0, s>>>(a);                       \
+    }                                                                                     \
+    break;
+  switch (a.W) {
+    HCL_CASE(2) HCL_CASE(3) HCL_CASE(4) HCL_CASE(5) HCL_CASE(6) HCL_CASE(7) HCL_CASE(8) HCL_CASE(9)
+    HCL_CASE(10) HCL_CASE(11) HCL_CASE(12) HCL_CASE(13) HCL_CASE(14) HCL_CASE(15) HCL_CASE(16)
+    default: return (int)hipErrorInvalidValue;
+  }
+#undef HCL_CASE
+  return (int)hipGetLastError();
+}
+template int launch_fused_sum<HCL_FUSED_DT>(const FusedArgs&, const Tuning&, void*);
+#else
+template <int DT>
+int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream) {
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const dim3 g(t.blocks), b(t.threads);
+  if (t.threads > kGenMaxThreads) return (int)hipErrorInvalidValue;
+#define HCL_CASE(WW)                                                              \
+  case WW:                                                                        \
+    if (t.nontemporal) ring_fused_gen<DT, WW, true><<<g, b, 0, s>>>(a);           \
+    else ring_fused_gen<DT, WW, false><<<g, b, 0, s>>>(a);                        \
+    break;
+  switch (a.W) {
+    HCL_CASE(2) HCL_CASE(3) HCL_CASE(4) HCL_CASE(5) HCL_CASE(6) HCL_CASE(7) HCL_CASE(8) HCL_CASE(9)
+    HCL_CASE(10) HCL_CASE(11) HCL_CASE(12) HCL_CASE(13) HCL_CASE(14) HCL_CASE(15) HCL_CASE(16)
+    default: return (int)hipErrorInvalidValue;
+  }
+#undef HCL_CASE
+  return (int)hipGetLastError();
+}
+template int launch_fused_gen<HCL_FUSED_DT>(const FusedArgs&, const Tuning&, void*);
+#endif
+
+}  // namespace hcl

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libhcl.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIAS, ERR_WORKSPACE, ERR_HIP = range(6)
 FP32, BF16, FP16, INT32 = 0, 1, 2, 3
-SUM = 0
+SUM, PROD, MAX, MIN = 0, 1, 2, 3
+OP = {"sum": SUM, "prod": PROD, "max": MAX, "min": MIN}
 SCHED_STEPWISE, SCHED_FUSED = 0, 1
 XPORT_DIRECT, XPORT_HOST_STAGED = 0, 1
 KIND_ALLREDUCE, KIND_REDUCE_SCATTER, KIND_ALL_GATHER, KIND_REDUCE, KIND_BROADCAST, KIND_ALLTOALL = range(6)
@@ -27,6 +28,8 @@ SCHED = {"stepwise": SCHED_STEPWISE, "fused": SCHED_FUSED}
 XPORT = {"direct": XPORT_DIRECT, "host_staged": XPORT_HOST_STAGED}
 ACC_PER_HOP, ACC_FP32 = 0, 1
 ACC = {"per_hop": ACC_PER_HOP, "fp32": ACC_FP32}
+ORDER_RING, ORDER_TREE = 0, 1
+ORDER = {"ring": ORDER_RING, "tree": ORDER_TREE}
 
 EXPORTS = [
     "hcl_allreduce_sim", "hcl_reduce_scatter_sim", "hcl_all_gather_sim", "hcl_reduce_sim",
@@ -62,6 +65,7 @@ class Opts(ctypes.Structure):
         ("events_per_phase", ctypes.c_int),
         ("n_launches", ctypes.POINTER(ctypes.c_int)),
         ("accumulate", ctypes.c_int),
+        ("order", ctypes.c_int),
     ]
 
 
@@ -166,7 +170,7 @@ class EventList:
 
 def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, host_stage=None,
               threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None,
-              events_per_phase=False, accumulate=0):
+              events_per_phase=False, accumulate=0, order=0):
     """Builds the hcl_opts_t struct.  Returns (opts, keepalive): keep `keepalive`
     referenced until the call has returned."""
     o = Opts()
@@ -188,6 +192,7 @@ def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, ho
     o.threads, o.blocks, o.unroll, o.nontemporal = int(threads), int(blocks), int(unroll), int(nontemporal)
     o.fuse_rs_ag = 1 if fuse_rs_ag else 0
     o.accumulate = ACC[accumulate] if isinstance(accumulate, str) else int(accumulate)
+    o.order = ORDER[order] if isinstance(order, str) else int(order)
     if events is not None:
         # an EventList, or (EventList, first, n) to use a slice of it
         ev, first, n = events if isinstance(events, tuple) else (events, 0, events.n)
@@ -209,6 +214,10 @@ def _dtype_code(tensors, dtype):
     return DTYPE_OF_TORCH[tensors[0].dtype]
 
 
+def _op_code(op):
+    return OP[op] if isinstance(op, str) else int(op)
+
+
 def _ptrs(tensors):
     return _ptr_array([None if t is None else t.data_ptr() for t in tensors])
 
@@ -218,7 +227,7 @@ def allreduce_sim(send, recv, chunk_bytes=0, dtype=None, op=SUM, stream=None, co
     W = len(send)
     o, keep = make_opts(W, **opt)
     n = send[0].numel() if count is None else count
-    _check(lib().hcl_allreduce_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), op,
+    _check(lib().hcl_allreduce_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), _op_code(op),
                                    chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
     return o.n_launches.contents.value
 
@@ -228,7 +237,7 @@ def reduce_scatter_sim(send, recv, chunk_bytes=0, dtype=None, op=SUM, stream=Non
     W = len(send)
     o, keep = make_opts(W, **opt)
     n = recv[0].numel() if recvcount is None else recvcount
-    _check(lib().hcl_reduce_scatter_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), op,
+    _check(lib().hcl_reduce_scatter_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), _op_code(op),
                                         chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
     return o.n_launches.contents.value
 
@@ -248,7 +257,7 @@ def reduce_sim(send, recv, root, chunk_bytes=0, dtype=None, op=SUM, stream=None,
     W = len(send)
     o, keep = make_opts(W, **opt)
     n = send[0].numel() if count is None else count
-    _check(lib().hcl_reduce_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), op, root,
+    _check(lib().hcl_reduce_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), _op_code(op), root,
                                 chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
     return o.n_launches.contents.value
 

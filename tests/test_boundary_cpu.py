@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     L = hcl.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert hcl.version() == 100
+    assert hcl.version() == 101
 
 
 def _call_ar(send, recv, W, count, dtype=hcl.FP32, op=hcl.SUM, chunk=0, **opt):
@@ -60,7 +60,10 @@ def test_allreduce_validation_codes():
     assert _call_ar([s[0], 0, s[2], s[3]], r, 4, 16) == hcl.ERR_INVALID_ARG  # null rank buffer
     assert _call_ar([s[0] + 2, s[1], s[2], s[3]], r, 4, 16) == hcl.ERR_INVALID_ARG  # misaligned for fp32
     assert _call_ar(s, r, 4, 16, chunk=6) == hcl.ERR_INVALID_ARG           # not a multiple of 4
-    assert _call_ar(s, r, 4, 16, op=1) == hcl.ERR_UNSUPPORTED
+    assert _call_ar(s, r, 4, 16, op=4) == hcl.ERR_UNSUPPORTED                # beyond sum, prod, max, min
+    assert _call_ar(s, r, 4, 16, op=-1) == hcl.ERR_UNSUPPORTED
+    assert _call_ar(s, r, 4, 16, order="tree") == hcl.ERR_UNSUPPORTED         # stepwise adds in ring order
+    assert _call_ar(s, r, 4, 16, sched="fused", order=2) == hcl.ERR_UNSUPPORTED
     assert _call_ar(s, r, 4, 16, dtype=7) == hcl.ERR_UNSUPPORTED
     assert _call_ar(s, r, 4, 16, ring=[0, 1, 2, 2]) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 16, ring=[0, 1, 2, 4]) == hcl.ERR_INVALID_ARG
@@ -201,7 +204,7 @@ def test_other_collectives_validation_codes():
     assert L.hcl_alltoall_sim(ps, pr, 4, 0, hcl.FP32, 0, ctypes.byref(o), None) == hcl.OK
     # bad root, bad op, missing workspace, staged transport, aliasing
     assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, hcl.SUM, 4, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
-    assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, 1, 0, 0, ctypes.byref(o), None) == hcl.ERR_UNSUPPORTED
+    assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, 9, 0, 0, ctypes.byref(o), None) == hcl.ERR_UNSUPPORTED
     assert L.hcl_reduce_sim(ps, pr, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_WORKSPACE
     assert L.hcl_broadcast_sim(ps, pr, 4, 16, hcl.FP32, -1, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
     st, keep2 = hcl.make_opts(4, xport="host_staged")

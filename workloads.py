@@ -64,6 +64,12 @@ def fill_rank(out, seed, dist, slab=1 << 24):
             t = torch.empty(m, dtype=torch.float32, device=out.device).normal_(dist[1], dist[2], generator=gen)
         elif kind == "randint":
             t = torch.randint(int(dist[1]), int(dist[2]) + 1, (m,), generator=gen, device=out.device)
+        elif kind == "bits":
+            # uniformly random bit patterns: every exponent, subnormals, infinities, NaNs, both zeros
+            width = out.element_size() * 8
+            raw = torch.randint(-(1 << (width - 1)), 1 << (width - 1), (m,), generator=gen, device=out.device)
+            out[lo:lo + m].view({16: torch.int16, 32: torch.int32}[width]).copy_(raw)
+            continue
         else:
             raise ValueError(kind)
         out[lo:lo + m].copy_(t)
