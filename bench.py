@@ -403,6 +403,24 @@ def main():
                     "hbm_kernel": roof}
         ev.close()
 
+    # ---- a measured copy ceiling beside the datasheet peak: the library's plain-copy kernel moving
+    # the same buffers (All-to-All: every block read once and written once), outside the timed region
+    if roof is not None and roof.get("bound") == "hbm" and op == "allreduce" and not args.inplace and count % W == 0 \
+            and not staged and S >= (64 << 20):
+        cev = hcl.EventList(2)
+        reps = 5
+        hcl.alltoall_sim(send, recv, chunk_bytes=chunk_bytes, stream=stream)
+        cev.record(0, stream)
+        for _ in range(reps):
+            hcl.alltoall_sim(send, recv, chunk_bytes=chunk_bytes, stream=stream)
+        cev.record(1, stream)
+        torch.cuda.synchronize()
+        copy_gbps = reps * 2 * W * S / (cev.elapsed_ms(0, 1) * 1e-3) / 1e9
+        cev.close()
+        roof["copy_ceiling"] = {"achieved": round(copy_gbps, 1), "unit": "GB/s",
+                                "what": "plain copy of the same buffers by reduce_copy_vec<copy,1,1> (W launches, gaps included)",
+                                "frac_of_it": round(roof["achieved"] / copy_gbps, 4)}
+
     value = S / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "ring all-reduce algorithm GB/s on 1 MI355X" if op == "allreduce"

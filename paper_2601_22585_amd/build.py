@@ -66,6 +66,21 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
+def build_examples(verbose=False):
+    """Compile the plain-C example against the built library (it links libhcl.so by path)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    src = os.path.join(HERE, "examples", "allreduce_latency.c")
+    exe = os.path.join(HERE, "examples", "allreduce_latency")
+    cmd = ["gcc", "-O2", "-std=gnu11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), src, LIB, "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return exe
+
+
 if __name__ == "__main__":
     build_lib(force=True, verbose=True)
     print(LIB)
+    print(build_examples(verbose=True))
