@@ -49,6 +49,9 @@
  *     for maximum / minimum, which follow IEEE 754-2019 clause 9.6: a NaN
  *     operand gives NaN, and -0 orders below +0.  int32: the product wraps
  *     modulo 2^32, maximum / minimum compare as signed integers.
+ *   - Further wire types: fp64 (one IEEE binary64 operation per hop, no
+ *     widening, nothing to round afterwards), int64 (wraps modulo 2^64, signed
+ *     comparisons) and uint8 (wraps modulo 2^8, unsigned comparisons).
  *   - Tree order (a reordered-class variant, like binary32 accumulation): the
  *     ranks' values are taken in ring order ring[0], ring[1], ..., ring[W-1] --
  *     the same order for every block -- and combined level by level, neighbours
@@ -80,7 +83,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_FP32 = 0, ORC_BF16 = 1, ORC_FP16 = 2, ORC_INT32 = 3 };
+enum { ORC_FP32 = 0, ORC_BF16 = 1, ORC_FP16 = 2, ORC_INT32 = 3, ORC_FP64 = 4, ORC_INT64 = 5, ORC_UINT8 = 6 };
 enum { ORC_OK = 0, ORC_BAD_ARG = 1, ORC_NO_MEM = 2 };
 enum { ORC_PHASE_RS = 0, ORC_PHASE_AG = 1 };
 enum { ORC_SUM = 0, ORC_PROD = 1, ORC_MAX = 2, ORC_MIN = 3 };
@@ -214,6 +217,43 @@ static int32_t i32_apply(int op, int32_t a, int32_t b)
     default:       return (int32_t)((uint32_t)a + (uint32_t)b);
     }
 }
+/* the same operators on the wider and narrower wire types */
+static double f64_apply(int op, double a, double b)
+{
+    switch (op) {
+    case ORC_PROD: return a * b;
+    case ORC_MAX:
+        if (isnan(a) || isnan(b)) return (double)NAN;
+        if (a > b) return a;
+        if (b > a) return b;
+        return signbit(a) ? b : a;
+    case ORC_MIN:
+        if (isnan(a) || isnan(b)) return (double)NAN;
+        if (a < b) return a;
+        if (b < a) return b;
+        return signbit(a) ? a : b;
+    default: return a + b;
+    }
+}
+static int64_t i64_apply(int op, int64_t a, int64_t b)
+{
+    switch (op) {
+    case ORC_PROD: return (int64_t)((uint64_t)a * (uint64_t)b);
+    case ORC_MAX:  return a > b ? a : b;
+    case ORC_MIN:  return a < b ? a : b;
+    default:       return (int64_t)((uint64_t)a + (uint64_t)b);
+    }
+}
+static uint8_t u8_apply(int op, uint8_t a, uint8_t b)
+{
+    switch (op) {
+    case ORC_PROD: return (uint8_t)(((unsigned)a * (unsigned)b) & 0xFFu);
+    case ORC_MAX:  return a > b ? a : b;
+    case ORC_MIN:  return a < b ? a : b;
+    default:       return (uint8_t)(((unsigned)a + (unsigned)b) & 0xFFu);
+    }
+}
+
 /* widen a wire element to binary32 (exact) and round binary32 to the wire type */
 static float wire_to_f32(const void *p, size_t i, int dtype)
 {
@@ -245,6 +285,24 @@ static void hop_run_op(void *local, const void *inbox, size_t n, int dtype, int 
         for (i = 0; i < nn; ++i) l[i] = i32_apply(op, in[i], l[i]);
         return;
     }
+    if (dtype == ORC_FP64) {
+        double *l = (double *)local; const double *in = (const double *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = f64_apply(op, in[i], l[i]);
+        return;
+    }
+    if (dtype == ORC_INT64) {
+        int64_t *l = (int64_t *)local; const int64_t *in = (const int64_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = i64_apply(op, in[i], l[i]);
+        return;
+    }
+    if (dtype == ORC_UINT8) {
+        uint8_t *l = (uint8_t *)local; const uint8_t *in = (const uint8_t *)inbox;
+        #pragma omp parallel for schedule(static) if (nn > 32768)
+        for (i = 0; i < nn; ++i) l[i] = u8_apply(op, in[i], l[i]);
+        return;
+    }
     #pragma omp parallel for schedule(static) if (nn > 32768)
     for (i = 0; i < nn; ++i) {
         float a = wire_to_f32(inbox, (size_t)i, dtype), b = wire_to_f32(local, (size_t)i, dtype);
@@ -256,6 +314,7 @@ static void hop_run_op(void *local, const void *inbox, size_t n, int dtype, int 
 static void hop_run(void *local, const void *inbox, size_t n, int dtype)
 {
     ptrdiff_t i, nn = (ptrdiff_t)n;
+    if (dtype >= ORC_FP64) { hop_run_op(local, inbox, n, dtype, ORC_SUM); return; }
     switch (dtype) {
     case ORC_FP32: {
         float *l = (float *)local; const float *in = (const float *)inbox;
@@ -294,7 +353,15 @@ static void copy_run(void *dst, const void *src, size_t nbytes)
 /* ------------------------------------------------------------------ */
 static int wrap(int a, int W) { a %= W; return a < 0 ? a + W : a; }
 
-size_t orc_esize(int dtype) { return (dtype == ORC_BF16 || dtype == ORC_FP16) ? 2u : 4u; }
+size_t orc_esize(int dtype)
+{
+    switch (dtype) {
+    case ORC_BF16: case ORC_FP16: return 2u;
+    case ORC_FP64: case ORC_INT64: return 8u;
+    case ORC_UINT8: return 1u;
+    default: return 4u;
+    }
+}
 
 static int ring_ok(int W, const int *ring, int *pos)
 {
@@ -386,7 +453,7 @@ static int ring_phase(void *const *work, int W, size_t count, size_t B, int dtyp
     return ORC_OK;
 }
 
-static int args_ok(int W, int dtype) { return W >= 1 && W <= 64 && dtype >= 0 && dtype <= 3; }
+static int args_ok(int W, int dtype) { return W >= 1 && W <= 64 && dtype >= 0 && dtype <= ORC_UINT8; }
 static int op_ok(int op) { return op >= ORC_SUM && op <= ORC_MIN; }
 
 /* All-Reduce with operator `op`, in place on work[r]: on entry rank r's input,
@@ -567,7 +634,7 @@ int orc_allreduce_fp32acc(const void *const *in, void *const *out, int W, size_t
                           const int *ring)
 {
     int pos[64], order[64];
-    if (!args_ok(W, dtype) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    if (!args_ok(W, dtype) || dtype > ORC_INT32 || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
     size_t es = orc_esize(dtype), B = (count + (size_t)W - 1) / (size_t)W;
     for (int c = 0; c < W; ++c) {
         size_t lo, hi;
@@ -584,7 +651,7 @@ int orc_reduce_scatter_fp32acc(const void *const *in, void *const *out, int W, s
                                const int *ring)
 {
     int pos[64], order[64];
-    if (!args_ok(W, dtype) || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    if (!args_ok(W, dtype) || dtype > ORC_INT32 || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
     for (int c = 0; c < W; ++c) {
         for (int k = 0; k < W; ++k) order[k] = ring_at(ring, wrap(pos[c] + 1 + k, W));
         sum_fp32acc_run(in, order, W, (size_t)c * n, n, dtype, out[c]);
@@ -597,7 +664,7 @@ int orc_reduce_fp32acc(const void *const *in, void *out, int W, size_t count, in
                        const int *ring, int root)
 {
     int pos[64], order[64];
-    if (!args_ok(W, dtype) || root < 0 || root >= W || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
+    if (!args_ok(W, dtype) || dtype > ORC_INT32 || root < 0 || root >= W || !ring_ok(W, ring, pos)) return ORC_BAD_ARG;
     for (int k = 0; k < W; ++k) order[k] = ring_at(ring, wrap(pos[root] + 1 + k, W));
     sum_fp32acc_run(in, order, W, 0, count, dtype, out);
     return ORC_OK;
@@ -651,6 +718,29 @@ static int32_t combine_i32(int32_t *v, int W, int op, int order)
     }
     return v[0];
 }
+/* the same shapes for the wire types that are their own accumulation type: no rounding step */
+#define ORC_COMBINE(NAME, T, APPLY)                                              \
+static T NAME(T *v, int W, int op, int order)                                    \
+{                                                                                \
+    if (order == ORC_ORDER_RING) {                                               \
+        T acc = v[0];                                                            \
+        for (int k = 1; k < W; ++k) acc = APPLY(op, acc, v[k]);                  \
+        return acc;                                                              \
+    }                                                                            \
+    int n = W;                                                                   \
+    while (n > 1) {                                                              \
+        int m = 0;                                                               \
+        for (int k = 0; k + 1 < n; k += 2) v[m++] = APPLY(op, v[k], v[k + 1]);   \
+        if (n & 1) v[m++] = v[n - 1];                                            \
+        n = m;                                                                   \
+    }                                                                            \
+    return v[0];                                                                 \
+}
+ORC_COMBINE(combine_f64, double, f64_apply)
+ORC_COMBINE(combine_i64, int64_t, i64_apply)
+ORC_COMBINE(combine_u8, uint8_t, u8_apply)
+#undef ORC_COMBINE
+
 /* out[i] = combination of in[who[k]][off + i], k = 0..W-1, for i in [0, n) */
 static void combine_run(const void *const *in, const int *who, int W, size_t off, size_t n, int dtype,
                         int op, int order, int rounding, void *out)
@@ -662,6 +752,18 @@ static void combine_run(const void *const *in, const int *who, int W, size_t off
             int32_t v[64];
             for (int k = 0; k < W; ++k) v[k] = ((const int32_t *)in[who[k]])[off + (size_t)i];
             ((int32_t *)out)[i] = combine_i32(v, W, op, order);
+        } else if (dtype == ORC_FP64) {
+            double v[64];
+            for (int k = 0; k < W; ++k) v[k] = ((const double *)in[who[k]])[off + (size_t)i];
+            ((double *)out)[i] = combine_f64(v, W, op, order);
+        } else if (dtype == ORC_INT64) {
+            int64_t v[64];
+            for (int k = 0; k < W; ++k) v[k] = ((const int64_t *)in[who[k]])[off + (size_t)i];
+            ((int64_t *)out)[i] = combine_i64(v, W, op, order);
+        } else if (dtype == ORC_UINT8) {
+            uint8_t v[64];
+            for (int k = 0; k < W; ++k) v[k] = ((const uint8_t *)in[who[k]])[off + (size_t)i];
+            ((uint8_t *)out)[i] = combine_u8(v, W, op, order);
         } else {
             float v[64];
             for (int k = 0; k < W; ++k) v[k] = wire_to_f32(in[who[k]], off + (size_t)i, dtype);

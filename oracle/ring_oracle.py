@@ -4,9 +4,9 @@ TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
 CPU-baseline leg of the benchmark; never by the product package.  It shares no
 code with the HIP path and does not import it.
 
-Wire types are passed as numpy arrays: float32 for fp32, int32 for int32 and
-uint16 bit patterns for bf16 / fp16 (numpy has no bfloat16, and bit patterns
-keep comparisons exact).
+Wire types are passed as numpy arrays: float32 / float64 / int32 / int64 /
+uint8 as themselves and uint16 bit patterns for bf16 / fp16 (numpy has no
+bfloat16, and bit patterns keep comparisons exact).
 """
 import ctypes
 import os
@@ -14,12 +14,13 @@ import subprocess
 
 import numpy as np
 
-FP32, BF16, FP16, INT32 = 0, 1, 2, 3
+FP32, BF16, FP16, INT32, FP64, INT64, UINT8 = 0, 1, 2, 3, 4, 5, 6
 PHASE_RS, PHASE_AG = 0, 1
 SUM, PROD, MAX, MIN = 0, 1, 2, 3
 ORDER_RING, ORDER_TREE = 0, 1
 ROUND_EACH, ROUND_ONCE = 0, 1
-NP_WIRE = {FP32: np.float32, BF16: np.uint16, FP16: np.uint16, INT32: np.int32}
+NP_WIRE = {FP32: np.float32, BF16: np.uint16, FP16: np.uint16, INT32: np.int32,
+           FP64: np.float64, INT64: np.int64, UINT8: np.uint8}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ring_oracle.c")

@@ -10,7 +10,9 @@ and ends with rank c, rounding to the wire type after every addition
 from fractions import Fraction
 
 # (exponent bits, fraction bits)
-FMT = {"fp32": (8, 23), "bf16": (8, 7), "fp16": (5, 10)}
+FMT = {"fp32": (8, 23), "bf16": (8, 7), "fp16": (5, 10), "fp64": (11, 52)}
+# integer wire types: (bits, signed)
+INT = {"int32": (32, True), "int64": (64, True), "uint8": (8, False)}
 
 
 def decode(bits, fmt):
@@ -94,7 +96,10 @@ def widen(bits, fmt):
 
 
 def hop(incoming_bits, local_bits, fmt):
-    """One ring hop: widen both to binary32, add with one rounding, round to the wire type."""
+    """One ring hop: widen both to binary32, add with one rounding, round to the wire type
+    (fp64: one binary64 addition)."""
+    if fmt == "fp64":
+        return add_round(incoming_bits, local_bits, "fp64", "fp64")
     s32 = add_round(widen(incoming_bits, fmt), widen(local_bits, fmt), "fp32", "fp32")
     d = decode(s32, "fp32")
     eb, fb = FMT[fmt]
@@ -134,7 +139,7 @@ def allreduce(inputs, fmt, ring=None):
         for i in range(lo, hi):
             acc = inputs[order[0]][i]
             for r in order[1:]:
-                acc = hop_int32(acc, inputs[r][i]) if fmt == "int32" else hop(acc, inputs[r][i], fmt)
+                acc = node_int(acc, inputs[r][i], "sum", fmt) if fmt in INT else hop(acc, inputs[r][i], fmt)
             out[i] = acc
     return out
 
@@ -148,7 +153,7 @@ def reduce(inputs, fmt, root, ring=None):
     for i in range(len(inputs[0])):
         acc = inputs[order[0]][i]
         for r in order[1:]:
-            acc = hop_int32(acc, inputs[r][i]) if fmt == "int32" else hop(acc, inputs[r][i], fmt)
+            acc = node_int(acc, inputs[r][i], "sum", fmt) if fmt in INT else hop(acc, inputs[r][i], fmt)
         out.append(acc)
     return out
 
@@ -239,13 +244,26 @@ def node(a_bits, b_bits, fmt, op):
     return pick_extreme(a_bits, b_bits, fmt, op == "max")
 
 
+def node_int(a, b, op, fmt="int32"):
+    """Integer hop: sum and product wrap modulo 2^bits (two's complement when signed)."""
+    bits, signed = INT[fmt]
+    if op in ("max", "min"):
+        return max(a, b) if op == "max" else min(a, b)
+    s = (a + b if op == "sum" else a * b) & ((1 << bits) - 1)
+    return s - (1 << bits) if signed and s >= (1 << (bits - 1)) else s
+
+
 def node_int32(a, b, op):
+    return node_int(a, b, op, "int32")
+
+
+def node64(a, b, op):
+    """One fp64 hop: a single IEEE binary64 operation, nothing to widen or narrow."""
     if op == "sum":
-        return hop_int32(a, b)
+        return add_round(a, b, "fp64", "fp64")
     if op == "prod":
-        s = (a * b) & 0xFFFFFFFF
-        return s - (1 << 32) if s >= (1 << 31) else s
-    return max(a, b) if op == "max" else min(a, b)
+        return mul_round(a, b, "fp64", "fp64")
+    return pick_extreme(a, b, "fp64", op == "max")
 
 
 def node32(a32, b32, op):
@@ -269,8 +287,11 @@ def narrow(x32, fmt):
 def combine(vals, fmt, op="sum", order="ring", rounding="each"):
     """vals: wire bit patterns (ints for int32) in the order they enter.  Ring: left fold.
     Tree: neighbours first, level by level, an odd last value moves up unchanged."""
-    if fmt == "int32":
-        f = lambda a, b: node_int32(a, b, op)
+    if fmt in INT:
+        f = lambda a, b: node_int(a, b, op, fmt)
+    elif fmt == "fp64":
+        f = lambda a, b: node64(a, b, op)
+        rounding = "each"          # the wire type is the accumulation type: nothing to round later
     elif rounding == "each":
         f = lambda a, b: node(a, b, fmt, op)
     else:
@@ -288,7 +309,7 @@ def combine(vals, fmt, op="sum", order="ring", rounding="each"):
                 nxt.append(vals[-1])
             vals = nxt
         acc = vals[0]
-    if fmt != "int32" and rounding != "each":
+    if fmt not in INT and rounding != "each":
         acc = narrow(acc, fmt)
     return acc
 

@@ -17,7 +17,8 @@ from test_oracle_ring import CODE, GOLDEN, _bits, _from_values, _random_wire, _t
 OPS = {"sum": orc.SUM, "prod": orc.PROD, "max": orc.MAX, "min": orc.MIN}
 ORDERS = {"ring": orc.ORDER_RING, "tree": orc.ORDER_TREE}
 ROUNDINGS = {"each": orc.ROUND_EACH, "once": orc.ROUND_ONCE}
-NAN_MASK = {"fp32": (0x7FFFFFFF, 0x7F800000), "bf16": (0x7FFF, 0x7F80), "fp16": (0x7FFF, 0x7C00)}
+NAN_MASK = {"fp32": (0x7FFFFFFF, 0x7F800000), "bf16": (0x7FFF, 0x7F80), "fp16": (0x7FFF, 0x7C00),
+            "fp64": (0x7FFFFFFFFFFFFFFF, 0x7FF0000000000000)}
 
 
 def _same(got_bits, want_bits, dtype):
@@ -36,17 +37,18 @@ def _rows(name):
 def _sym(tok, dtype):
     """golden-file symbol -> wire bit pattern"""
     if tok == "nan":
-        return int(_from_values([np.nan], dtype).view(np.uint32 if dtype == "fp32" else np.uint16)[0])
+        return _bits(_from_values([np.nan], dtype), dtype)[0]
     v = {"+inf": np.inf, "-inf": -np.inf, "inf": np.inf, "+0": 0.0, "-0": -0.0}.get(tok)
     if v is None:
         v = float(tok)
-    a = _from_values([v], dtype)
-    return int(a.view(np.uint32)[0]) if dtype == "fp32" else int(a[0])
+    return _bits(_from_values([v], dtype), dtype)[0]
 
 
 def _wire_of_bits(bits, dtype):
     if dtype == "fp32":
         return np.array(bits, dtype=np.uint32).view(np.float32)
+    if dtype == "fp64":
+        return np.array(bits, dtype=np.uint64).view(np.float64)
     if dtype == "int32":
         return np.array(bits, dtype=np.int32)
     return np.array(bits, dtype=np.uint16)
@@ -146,7 +148,7 @@ def test_tree_cancellation_example(row):
         assert np.all(_to_values(once[r], dtype) == float(row[3]))
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16", "fp64"])
 def test_maximum_minimum_of_special_operands(dtype):
     rows = _rows("minmax_specials.txt")
     a = _wire_of_bits([_sym(r[0], dtype) for r in rows], dtype)

@@ -10,7 +10,8 @@ import torch
 import brute
 from oracle import ring_oracle as orc
 
-CODE = {"fp32": orc.FP32, "bf16": orc.BF16, "fp16": orc.FP16, "int32": orc.INT32}
+CODE = {"fp32": orc.FP32, "bf16": orc.BF16, "fp16": orc.FP16, "int32": orc.INT32,
+        "fp64": orc.FP64, "int64": orc.INT64, "uint8": orc.UINT8}
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
@@ -23,6 +24,12 @@ def _from_values(vals, dtype):
         return v.astype(np.float16).view(np.uint16)
     if dtype == "bf16":
         return torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    if dtype == "fp64":
+        return v.copy()
+    if dtype == "int64":
+        return v.astype(np.int64)
+    if dtype == "uint8":
+        return v.astype(np.int64).astype(np.uint8)      # wraps modulo 256
     return v.astype(np.int32)
 
 
@@ -37,6 +44,8 @@ def _to_values(a, dtype):
 def _bits(a, dtype):
     if dtype == "fp32":
         return [int(x) for x in a.view(np.uint32)]
+    if dtype == "fp64":
+        return [int(x) for x in a.view(np.uint64)]
     return [int(x) for x in a]
 
 
@@ -140,6 +149,10 @@ def test_cancellation_example(dtype, M, blocks):
 def _random_wire(rng, n, dtype):
     if dtype == "int32":
         return rng.integers(-2**31, 2**31, size=n, dtype=np.int64).astype(np.int32)
+    if dtype == "int64":
+        return rng.integers(-2**63, 2**63 - 1, size=n, dtype=np.int64, endpoint=True)
+    if dtype == "uint8":
+        return rng.integers(0, 256, size=n, dtype=np.int64).astype(np.uint8)
     # moderate exponent spread so that most additions round; a few huge / tiny values
     mant = rng.standard_normal(n) * np.exp2(rng.integers(-3, 4, size=n))
     if dtype == "fp16":
