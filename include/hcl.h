@@ -20,7 +20,7 @@
  *     device or pinned memory; scratch comes in through hcl_opts_t.
  *   - Ring: ring[] is a permutation of 0..W-1 (NULL = identity); rank ring[k]
  *     sends to rank ring[(k+1) mod W].
- *   - Result bits.  int32 sums wrap modulo 2^32.  For the float types every
+ *   - Result bits.  Integer sums wrap modulo 2^bits.  For fp32 / bf16 / fp16 every
  *     hop computes round_T(f32(incoming) + f32(local)) with round to nearest
  *     even, subnormals kept, overflow to infinity, NaN propagated (any NaN
  *     pattern).  Block c's sum starts with the rank after c in the ring and
@@ -61,7 +61,7 @@ extern "C" {
 #endif
 
 #define HCL_MAX_RANKS 16
-#define HCL_VERSION 101
+#define HCL_VERSION 102
 
 typedef enum {
   HCL_OK = 0,
@@ -73,7 +73,13 @@ typedef enum {
   HCL_ERR_HIP = 5          /* a HIP runtime call failed */
 } hcl_status_t;
 
-typedef enum { HCL_FP32 = 0, HCL_BF16 = 1, HCL_FP16 = 2, HCL_INT32 = 3 } hcl_dtype_t;
+/* Wire types.  fp32 / bf16 / fp16 hops compute in binary32 and round to the wire
+ * type; fp64 hops are one binary64 operation; the integer types wrap modulo
+ * 2^bits (int32, int64: signed comparisons; uint8: unsigned -- also the type for
+ * moving raw bytes of any format through All-Gather, Broadcast and All-to-All). */
+typedef enum {
+  HCL_FP32 = 0, HCL_BF16 = 1, HCL_FP16 = 2, HCL_INT32 = 3, HCL_FP64 = 4, HCL_INT64 = 5, HCL_UINT8 = 6
+} hcl_dtype_t;
 /* Reduction operator of one hop: partial = round_T(op(f32(incoming), f32(local))).
  * SUM and PROD round to nearest even (the product of two bf16 / fp16 values is
  * exact in binary32, so PROD is the correctly rounded product); MAX and MIN

@@ -37,7 +37,7 @@ def build_lib(force=True, verbose=False):
     # translation units: the API, the step kernels, and the fused kernels once per
     # (wire type, part) -- compiled side by side, then one link
     units = [("hcl_api.cpp", "hcl_api", []), ("reduce_copy.hip", "reduce_copy", [])]
-    for dt in range(4):
+    for dt in range(7):
         for part in range(2):
             units.append(("ring_fused.hip", f"ring_fused_dt{dt}_p{part}", [f"-DHCL_FUSED_DT={dt}", f"-DHCL_FUSED_PART={part}"]))
     objs, cmds = [], []

@@ -76,7 +76,7 @@ extern "C" hcl_status_t hcl_ring_step(int W, const int* ring, int phase, int ste
   return HCL_OK;
 }
 
-static bool dtype_ok(int d) { return d >= HCL_FP32 && d <= HCL_INT32; }
+static bool dtype_ok(int d) { return d >= HCL_FP32 && d <= HCL_UINT8; }
 
 extern "C" hcl_status_t hcl_schedule_items(int W, const int* ring, size_t count, hcl_dtype_t dtype,
                                            size_t chunk_bytes, int phase, int step,

@@ -72,7 +72,7 @@ constexpr int kGenMaxThreads = 256;
 int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& t, void* stream);
 int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream);
 
-// Per wire type (0 fp32, 1 bf16, 2 fp16, 3 int32), one object file each:
+// Per wire type (0 fp32, 1 bf16, 2 fp16, 3 int32, 4 fp64, 5 int64, 6 uint8), one object file each:
 // ring-order sums, copies and the element-wise path / the general form.
 template <int DT> int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream);
 template <int DT> int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream);

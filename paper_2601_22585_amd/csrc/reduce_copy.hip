@@ -8,6 +8,7 @@
 // stores.  A launch covers one tile per workgroup, or strides over the tiles
 // when the grid is capped.
 #include "wire.h"
+#include "ring_sched.h"
 
 namespace hcl {
 
@@ -103,7 +104,7 @@ __global__ void __launch_bounds__(1024) reduce_copy_elem(const StepArgs a, const
 // host-side dispatch
 // ---------------------------------------------------------------------------
 uint64_t tile_elems(int dtype, const Tuning& t) {
-  const uint32_t es = (dtype == DT_BF16 || dtype == DT_FP16) ? 2 : 4;
+  const uint32_t es = (uint32_t)elem_size(dtype);
   return (uint64_t)t.threads * (16 / es) * t.unroll;
 }
 
@@ -148,12 +149,22 @@ static int launch_step_d(const StepArgs& a, int nsrc, int ndst, const Tuning& t,
 int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& t, void* stream) {
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   // a copy moves bits: share the integer instantiations of the same element size
-  if (nsrc == 1) dtype = (dtype == DT_BF16 || dtype == DT_FP16) ? DT_BF16 : DT_INT32;
+  if (nsrc == 1) {
+    switch (elem_size(dtype)) {
+      case 1: dtype = DT_UINT8; break;
+      case 2: dtype = DT_BF16; break;
+      case 8: dtype = DT_INT64; break;
+      default: dtype = DT_INT32; break;
+    }
+  }
   switch (dtype) {
     case DT_FP32: return launch_step_d<DT_FP32>(a, nsrc, ndst, t, s);
     case DT_BF16: return launch_step_d<DT_BF16>(a, nsrc, ndst, t, s);
     case DT_FP16: return launch_step_d<DT_FP16>(a, nsrc, ndst, t, s);
     case DT_INT32: return launch_step_d<DT_INT32>(a, nsrc, ndst, t, s);
+    case DT_FP64: return launch_step_d<DT_FP64>(a, nsrc, ndst, t, s);
+    case DT_INT64: return launch_step_d<DT_INT64>(a, nsrc, ndst, t, s);
+    case DT_UINT8: return launch_step_d<DT_UINT8>(a, nsrc, ndst, t, s);
   }
   return (int)hipErrorInvalidValue;
 }
@@ -168,6 +179,9 @@ int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream) {
     case DT_BF16: return gen ? launch_fused_gen<DT_BF16>(a, t, stream) : launch_fused_sum<DT_BF16>(a, t, stream);
     case DT_FP16: return gen ? launch_fused_gen<DT_FP16>(a, t, stream) : launch_fused_sum<DT_FP16>(a, t, stream);
     case DT_INT32: return gen ? launch_fused_gen<DT_INT32>(a, t, stream) : launch_fused_sum<DT_INT32>(a, t, stream);
+    case DT_FP64: return gen ? launch_fused_gen<DT_FP64>(a, t, stream) : launch_fused_sum<DT_FP64>(a, t, stream);
+    case DT_INT64: return gen ? launch_fused_gen<DT_INT64>(a, t, stream) : launch_fused_sum<DT_INT64>(a, t, stream);
+    case DT_UINT8: return gen ? launch_fused_gen<DT_UINT8>(a, t, stream) : launch_fused_sum<DT_UINT8>(a, t, stream);
   }
   return (int)hipErrorInvalidValue;
 }

@@ -2,14 +2,14 @@
 // stays inside one thread, every rank's value is read once.
 //
 // This file is compiled once per (HCL_FUSED_DT, HCL_FUSED_PART): the wire type
-// (0 fp32, 1 bf16, 2 fp16, 3 int32) and the part -- 0: ring-order sums, the
+// (0 fp32, 1 bf16, 2 fp16, 3 int32, 4 fp64, 5 int64, 6 uint8) and the part -- 0: ring-order sums, the
 // All-Gather / Broadcast kernel and the element-wise path; 1: the general form
 // (run-time operator, tree order, rounding once).  Each object file holds one
 // explicit instantiation of launch_fused_sum<DT> or launch_fused_gen<DT>.
 #include "wire.h"
 
 #if !defined(HCL_FUSED_DT) || !defined(HCL_FUSED_PART)
-#error "compile with -DHCL_FUSED_DT=<0..3> -DHCL_FUSED_PART=<0|1>"
+#error "compile with -DHCL_FUSED_DT=<0..6> -DHCL_FUSED_PART=<0|1>"
 #endif
 
 namespace hcl {
@@ -134,12 +134,19 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
     }
     const uint32_t e = nvec * VE + tid;
     if (e < len) {
-      if (ES == 2) {
+      // up to VE - 1 elements: the tail of a 16-byte vector (ES = 8 never gets here)
+      if (ES == 1) {
+        const uint8_t x = reinterpret_cast<const uint8_t*>(s)[e];
+        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint8_t*>(a.dst[r] + voff)[e] = x;
+      } else if (ES == 2) {
         const uint16_t x = reinterpret_cast<const uint16_t*>(s)[e];
         for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint16_t*>(a.dst[r] + voff)[e] = x;
-      } else {
+      } else if (ES == 4) {
         const uint32_t x = reinterpret_cast<const uint32_t*>(s)[e];
         for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint32_t*>(a.dst[r] + voff)[e] = x;
+      } else {
+        const uint64_t x = reinterpret_cast<const uint64_t*>(s)[e];
+        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint64_t*>(a.dst[r] + voff)[e] = x;
       }
     }
   }
@@ -171,14 +178,20 @@ __global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const
       elem_t acc;
       if (one_src) {
         acc = reinterpret_cast<const elem_t*>(a.src[c])[i];
-      } else if (DT == DT_INT32) {
-        uint32_t v[kMaxFusedRanks];
-        for (uint32_t k = 0; k < W; ++k) v[k] = (uint32_t)reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
+      } else if (DT == DT_INT32 || DT == DT_INT64 || DT == DT_UINT8 || DT == DT_FP64) {
+        // integers: 64-bit values, sign- or zero-extended, truncated to the element at the end;
+        // fp64: its bit pattern
+        uint64_t v[kMaxFusedRanks];
+        for (uint32_t k = 0; k < W; ++k) {
+          const elem_t x = reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
+          v[k] = DT == DT_INT32 ? (uint64_t)(int64_t)(int32_t)x : (uint64_t)x;
+        }
+        auto node = [&](uint64_t x, uint64_t y) { return op_elem64<DT == DT_FP64 ? DT_FP64 : DT_INT64>(op, x, y); };
         if (!tree) {
-          for (uint32_t k = 1; k < W; ++k) v[0] = apply_i32(op, v[0], v[k]);
+          for (uint32_t k = 1; k < W; ++k) v[0] = node(v[0], v[k]);
         } else {
           for (uint32_t n = W; n > 1; n = (n + 1) / 2) {
-            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = apply_i32(op, v[k], v[k + 1]);
+            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = node(v[k], v[k + 1]);
             if (n & 1) v[n / 2] = v[n - 1];
           }
         }
@@ -224,18 +237,18 @@ __global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const
 // ---------------------------------------------------------------------------
 template <int DT, int W>
 __device__ __forceinline__ uint32_t combine_word(const uint32_t (&w)[W], uint32_t op, bool tree, bool wide) {
-  if (DT == DT_INT32) {
+  if (DT == DT_INT32 || DT == DT_UINT8) {
     uint32_t v[W];
 #pragma unroll
     for (int k = 0; k < W; ++k) v[k] = w[k];
     if (!tree) {
 #pragma unroll
-      for (int k = 1; k < W; ++k) v[0] = apply_i32(op, v[0], v[k]);
+      for (int k = 1; k < W; ++k) v[0] = op_word<DT>(op, v[0], v[k]);
     } else {
 #pragma unroll
       for (int n = W; n > 1; n = (n + 1) / 2) {
 #pragma unroll
-        for (int k = 0; k + 1 < n; k += 2) v[k / 2] = apply_i32(op, v[k], v[k + 1]);
+        for (int k = 0; k + 1 < n; k += 2) v[k / 2] = op_word<DT>(op, v[k], v[k + 1]);
         if (n & 1) v[n / 2] = v[n - 1];
       }
     }
@@ -282,6 +295,59 @@ __device__ __forceinline__ uint32_t combine_word(const uint32_t (&w)[W], uint32_
   return kTwo ? Wire<DT>::narrow2(lo[0], hi[0]) : f2u(lo[0]);
 }
 
+// the same for one eight-byte element (fp64, int64): nothing to widen or round
+template <int DT, int W>
+__device__ __forceinline__ uint64_t combine64(const uint64_t (&w)[W], uint32_t op, bool tree) {
+  uint64_t v[W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) v[k] = w[k];
+  if (!tree) {
+#pragma unroll
+    for (int k = 1; k < W; ++k) v[0] = op_elem64<DT>(op, v[0], v[k]);
+  } else {
+#pragma unroll
+    for (int n = W; n > 1; n = (n + 1) / 2) {
+#pragma unroll
+      for (int k = 0; k + 1 < n; k += 2) v[k / 2] = op_elem64<DT>(op, v[k], v[k + 1]);
+      if (n & 1) v[n / 2] = v[n - 1];
+    }
+  }
+  return v[0];
+}
+
+// a whole 128-bit vector per rank
+template <int DT, int W>
+__device__ __forceinline__ u32x4 combine_vec(const u32x4 (&v)[W], uint32_t op, bool tree, bool wide) {
+  u32x4 acc;
+  if (sizeof(typename Wire<DT>::elem_t) == 8) {
+    uint64_t lo[W], hi[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+      lo[k] = (uint64_t)v[k].x | ((uint64_t)v[k].y << 32);
+      hi[k] = (uint64_t)v[k].z | ((uint64_t)v[k].w << 32);
+    }
+    const uint64_t a = combine64<DT, W>(lo, op, tree), b = combine64<DT, W>(hi, op, tree);
+    acc.x = (uint32_t)a;
+    acc.y = (uint32_t)(a >> 32);
+    acc.z = (uint32_t)b;
+    acc.w = (uint32_t)(b >> 32);
+    return acc;
+  }
+  uint32_t wx[W], wy[W], wz[W], ww[W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) {
+    wx[k] = v[k].x;
+    wy[k] = v[k].y;
+    wz[k] = v[k].z;
+    ww[k] = v[k].w;
+  }
+  acc.x = combine_word<DT, W>(wx, op, tree, wide);
+  acc.y = combine_word<DT, W>(wy, op, tree, wide);
+  acc.z = combine_word<DT, W>(wz, op, tree, wide);
+  acc.w = combine_word<DT, W>(ww, op, tree, wide);
+  return acc;
+}
+
 template <int DT, int W, bool NT>
 __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs a) {
   typedef typename Wire<DT>::elem_t elem_t;
@@ -318,19 +384,7 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
         u32x4 v[W];
 #pragma unroll
         for (int k = 0; k < W; ++k) v[k] = ld16<NT>(sp[k] + vi * 16u);
-        uint32_t wx[W], wy[W], wz[W], ww[W];
-#pragma unroll
-        for (int k = 0; k < W; ++k) {
-          wx[k] = v[k].x;
-          wy[k] = v[k].y;
-          wz[k] = v[k].z;
-          ww[k] = v[k].w;
-        }
-        u32x4 acc;
-        acc.x = combine_word<DT, W>(wx, op, tree, wide);
-        acc.y = combine_word<DT, W>(wy, op, tree, wide);
-        acc.z = combine_word<DT, W>(wz, op, tree, wide);
-        acc.w = combine_word<DT, W>(ww, op, tree, wide);
+        const u32x4 acc = combine_vec<DT, W>(v, op, tree, wide);
         if (to_all) {
 #pragma unroll
           for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
@@ -341,11 +395,19 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
     }
     const uint32_t e = nvec * VE + tid;
     if (e < len) {
-      // one element: put it into the low half of a word and combine words
-      uint32_t w1[W];
+      // one element: put it into the low bits of a word (or a 64-bit value) and combine those
+      elem_t acc;
+      if (sizeof(elem_t) == 8) {
+        uint64_t w1[W];
 #pragma unroll
-      for (int k = 0; k < W; ++k) w1[k] = (uint32_t)reinterpret_cast<const elem_t*>(sp[k])[e];
-      const elem_t acc = (elem_t)combine_word<DT, W>(w1, op, tree, wide);
+        for (int k = 0; k < W; ++k) w1[k] = (uint64_t)reinterpret_cast<const elem_t*>(sp[k])[e];
+        acc = (elem_t)combine64<DT, W>(w1, op, tree);
+      } else {
+        uint32_t w1[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) w1[k] = (uint32_t)reinterpret_cast<const elem_t*>(sp[k])[e];
+        acc = (elem_t)combine_word<DT, W>(w1, op, tree, wide);
+      }
       if (to_all) {
 #pragma unroll
         for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;

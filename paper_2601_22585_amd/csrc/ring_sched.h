@@ -45,6 +45,14 @@ struct BlockMap {
 };
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
-inline size_t elem_size(int dtype) { return (dtype == 1 || dtype == 2) ? 2u : 4u; }
+// bytes per element of a wire type: fp32 0, bf16 1, fp16 2, int32 3, fp64 4, int64 5, uint8 6
+inline size_t elem_size(int dtype) {
+  switch (dtype) {
+    case 1: case 2: return 2u;
+    case 4: case 5: return 8u;
+    case 6: return 1u;
+    default: return 4u;
+  }
+}
 
 }  // namespace hcl

@@ -2,7 +2,8 @@
 // access, the wire types' hop arithmetic, and the tile decomposition.
 //
 // Arithmetic of one hop (reductions run on the GPU, Appendix E.3):
-//   partial = round_T(op(f32(incoming), f32(local))), round to nearest even,
+//   partial = round_T(op(f32(incoming), f32(local))), round to nearest even
+// (fp64: one binary64 operation; integers wrap modulo 2^bits),
 // op = sum by default; product, maximum and minimum are the other operators of
 // the call shape (Section 4.4).  Maximum / minimum follow IEEE 754-2019 clause
 // 9.6: a NaN operand gives NaN, -0 orders below +0.
@@ -17,7 +18,7 @@ namespace hcl {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-enum { DT_FP32 = 0, DT_BF16 = 1, DT_FP16 = 2, DT_INT32 = 3 };
+enum { DT_FP32 = 0, DT_BF16 = 1, DT_FP16 = 2, DT_INT32 = 3, DT_FP64 = 4, DT_INT64 = 5, DT_UINT8 = 6 };
 
 // ---------------------------------------------------------------------------
 // memory access helpers
@@ -127,9 +128,49 @@ template <> struct Wire<DT_FP16> {
   }
 };
 
+// eight-byte types: a 128-bit vector holds two elements; hop_word is never used
+__device__ __forceinline__ uint64_t d2u(double d) { return (uint64_t)__double_as_longlong(d); }
+__device__ __forceinline__ double u2d(uint64_t u) { return __longlong_as_double((long long)u); }
+template <> struct Wire<DT_FP64> {
+  typedef uint64_t elem_t;
+  static constexpr bool kWide = false;
+  __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) { return d2u(u2d(in) + u2d(loc)); }
+  __device__ static __forceinline__ uint32_t hop_word(uint32_t, uint32_t) { return 0; }
+  __device__ static __forceinline__ void widen2(uint32_t, float&, float&) {}
+  __device__ static __forceinline__ uint32_t narrow2(float, float) { return 0; }
+};
+template <> struct Wire<DT_INT64> {
+  typedef uint64_t elem_t;
+  static constexpr bool kWide = false;
+  __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) { return in + loc; }
+  __device__ static __forceinline__ uint32_t hop_word(uint32_t, uint32_t) { return 0; }
+  __device__ static __forceinline__ void widen2(uint32_t, float&, float&) {}
+  __device__ static __forceinline__ uint32_t narrow2(float, float) { return 0; }
+};
+// one-byte type: four elements per word, added without carries between bytes
+template <> struct Wire<DT_UINT8> {
+  typedef uint8_t elem_t;
+  static constexpr bool kWide = false;
+  __device__ static __forceinline__ elem_t hop_elem(elem_t in, elem_t loc) { return (elem_t)(in + loc); }
+  __device__ static __forceinline__ uint32_t hop_word(uint32_t in, uint32_t loc) {
+    return ((in & 0x7F7F7F7Fu) + (loc & 0x7F7F7F7Fu)) ^ ((in ^ loc) & 0x80808080u);
+  }
+  __device__ static __forceinline__ void widen2(uint32_t, float&, float&) {}
+  __device__ static __forceinline__ uint32_t narrow2(float, float) { return 0; }
+};
+
 template <int DT>
 __device__ __forceinline__ u32x4 hop_vec(u32x4 in, u32x4 loc) {
   u32x4 r;
+  if (sizeof(typename Wire<DT>::elem_t) == 8) {
+    const uint64_t lo = Wire<DT>::hop_elem((uint64_t)in.x | ((uint64_t)in.y << 32), (uint64_t)loc.x | ((uint64_t)loc.y << 32));
+    const uint64_t hi = Wire<DT>::hop_elem((uint64_t)in.z | ((uint64_t)in.w << 32), (uint64_t)loc.z | ((uint64_t)loc.w << 32));
+    r.x = (uint32_t)lo;
+    r.y = (uint32_t)(lo >> 32);
+    r.z = (uint32_t)hi;
+    r.w = (uint32_t)(hi >> 32);
+    return r;
+  }
   r.x = Wire<DT>::hop_word(in.x, loc.x);
   r.y = Wire<DT>::hop_word(in.y, loc.y);
   r.z = Wire<DT>::hop_word(in.z, loc.z);
@@ -209,9 +250,54 @@ __device__ __forceinline__ uint32_t apply_i32(uint32_t op, uint32_t a, uint32_t 
   }
 }
 
+__device__ __forceinline__ double apply_f64(uint32_t op, double a, double b) {
+  switch (op) {
+    case OP_PROD: return a * b;
+    case OP_MAX: {
+      double m = a > b ? a : b;
+      if (a == b) m = (d2u(a) >> 63) ? b : a;
+      if (a != a || b != b) m = u2d(0x7FF8000000000000ull);
+      return m;
+    }
+    case OP_MIN: {
+      double m = a < b ? a : b;
+      if (a == b) m = (d2u(a) >> 63) ? a : b;
+      if (a != a || b != b) m = u2d(0x7FF8000000000000ull);
+      return m;
+    }
+    default: return a + b;
+  }
+}
+__device__ __forceinline__ uint64_t apply_i64(uint32_t op, uint64_t a, uint64_t b) {
+  switch (op) {
+    case OP_PROD: return a * b;
+    case OP_MAX: return (int64_t)a > (int64_t)b ? a : b;
+    case OP_MIN: return (int64_t)a < (int64_t)b ? a : b;
+    default: return a + b;
+  }
+}
+// four unsigned bytes at once
+__device__ __forceinline__ uint32_t apply_u8x4(uint32_t op, uint32_t a, uint32_t b) {
+  if (op == OP_SUM) return Wire<DT_UINT8>::hop_word(a, b);
+  uint32_t r = 0;
+#pragma unroll
+  for (int s = 0; s < 32; s += 8) {
+    const uint32_t x = (a >> s) & 0xFFu, y = (b >> s) & 0xFFu;
+    const uint32_t v = op == OP_PROD ? (x * y) & 0xFFu : (op == OP_MAX ? (x > y ? x : y) : (x < y ? x : y));
+    r |= v << s;
+  }
+  return r;
+}
+// one eight-byte element
+template <int DT>
+__device__ __forceinline__ uint64_t op_elem64(uint32_t op, uint64_t in, uint64_t loc) {
+  return DT == DT_FP64 ? d2u(apply_f64(op, u2d(in), u2d(loc))) : apply_i64(op, in, loc);
+}
+
 // One hop with a run-time operator on a 32-bit word / on one element.
 template <int DT>
 __device__ __forceinline__ uint32_t op_word(uint32_t op, uint32_t in, uint32_t loc) {
+  if (DT == DT_UINT8) return apply_u8x4(op, in, loc);
   if (DT == DT_INT32) return apply_i32(op, in, loc);
   if (DT == DT_FP32) return f2u(apply_f32(op, u2f(in), u2f(loc)));
   float a0, a1, b0, b1;
@@ -223,12 +309,22 @@ template <int DT>
 __device__ __forceinline__ typename Wire<DT>::elem_t op_elem(uint32_t op, typename Wire<DT>::elem_t in,
                                                              typename Wire<DT>::elem_t loc) {
   typedef typename Wire<DT>::elem_t elem_t;
-  if (sizeof(elem_t) == 4) return (elem_t)op_word<DT>(op, (uint32_t)in, (uint32_t)loc);
-  return (elem_t)(op_word<DT>(op, (uint32_t)in, (uint32_t)loc) & 0xFFFFu);
+  if (sizeof(elem_t) == 8) return (elem_t)op_elem64<DT>(op, (uint64_t)in, (uint64_t)loc);
+  // narrower than a word: the element sits in the low bits, the rest of the word is dropped
+  return (elem_t)op_word<DT>(op, (uint32_t)in, (uint32_t)loc);
 }
 template <int DT>
 __device__ __forceinline__ u32x4 op_vec(uint32_t op, u32x4 in, u32x4 loc) {
   u32x4 r;
+  if (sizeof(typename Wire<DT>::elem_t) == 8) {
+    const uint64_t lo = op_elem64<DT>(op, (uint64_t)in.x | ((uint64_t)in.y << 32), (uint64_t)loc.x | ((uint64_t)loc.y << 32));
+    const uint64_t hi = op_elem64<DT>(op, (uint64_t)in.z | ((uint64_t)in.w << 32), (uint64_t)loc.z | ((uint64_t)loc.w << 32));
+    r.x = (uint32_t)lo;
+    r.y = (uint32_t)(lo >> 32);
+    r.z = (uint32_t)hi;
+    r.w = (uint32_t)(hi >> 32);
+    return r;
+  }
   r.x = op_word<DT>(op, in.x, loc.x);
   r.y = op_word<DT>(op, in.y, loc.y);
   r.z = op_word<DT>(op, in.z, loc.z);

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhcl.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIAS, ERR_WORKSPACE, ERR_HIP = range(6)
-FP32, BF16, FP16, INT32 = 0, 1, 2, 3
+FP32, BF16, FP16, INT32, FP64, INT64, UINT8 = 0, 1, 2, 3, 4, 5, 6
 SUM, PROD, MAX, MIN = 0, 1, 2, 3
 OP = {"sum": SUM, "prod": PROD, "max": MAX, "min": MIN}
 SCHED_STEPWISE, SCHED_FUSED = 0, 1
@@ -23,7 +23,8 @@ KIND_ALLREDUCE, KIND_REDUCE_SCATTER, KIND_ALL_GATHER, KIND_REDUCE, KIND_BROADCAS
 PHASE_RS, PHASE_AG = 0, 1
 MAX_RANKS = 16
 
-DTYPE_OF_TORCH = {torch.float32: FP32, torch.bfloat16: BF16, torch.float16: FP16, torch.int32: INT32}
+DTYPE_OF_TORCH = {torch.float32: FP32, torch.bfloat16: BF16, torch.float16: FP16, torch.int32: INT32,
+                  torch.float64: FP64, torch.int64: INT64, torch.uint8: UINT8}
 SCHED = {"stepwise": SCHED_STEPWISE, "fused": SCHED_FUSED}
 XPORT = {"direct": XPORT_DIRECT, "host_staged": XPORT_HOST_STAGED}
 ACC_PER_HOP, ACC_FP32 = 0, 1

@@ -17,9 +17,10 @@ import torch
 
 KiB, MiB, GiB = 1 << 10, 1 << 20, 1 << 30
 
-TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16, "fp16": torch.float16, "int32": torch.int32}
-ESIZE = {"fp32": 4, "bf16": 2, "fp16": 2, "int32": 4}
-DTYPE_CODE = {"fp32": 0, "bf16": 1, "fp16": 2, "int32": 3}
+TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16, "fp16": torch.float16, "int32": torch.int32,
+               "fp64": torch.float64, "int64": torch.int64, "uint8": torch.uint8}
+ESIZE = {"fp32": 4, "bf16": 2, "fp16": 2, "int32": 4, "fp64": 8, "int64": 8, "uint8": 1}
+DTYPE_CODE = {"fp32": 0, "bf16": 1, "fp16": 2, "int32": 3, "fp64": 4, "int64": 5, "uint8": 6}
 
 # The five workload families.  `count` is elements per rank buffer.
 CONFIGS = {
@@ -64,11 +65,17 @@ def fill_rank(out, seed, dist, slab=1 << 24):
             t = torch.empty(m, dtype=torch.float32, device=out.device).normal_(dist[1], dist[2], generator=gen)
         elif kind == "randint":
             t = torch.randint(int(dist[1]), int(dist[2]) + 1, (m,), generator=gen, device=out.device)
+            if out.dtype == torch.uint8:
+                t = t & 0xFF            # two's-complement wrap into the byte range
         elif kind == "bits":
             # uniformly random bit patterns: every exponent, subnormals, infinities, NaNs, both zeros
             width = out.element_size() * 8
-            raw = torch.randint(-(1 << (width - 1)), 1 << (width - 1), (m,), generator=gen, device=out.device)
-            out[lo:lo + m].view({16: torch.int16, 32: torch.int32}[width]).copy_(raw)
+            if width == 8:
+                out[lo:lo + m].copy_(torch.randint(0, 256, (m,), generator=gen, device=out.device))
+                continue
+            top = (1 << (width - 1)) - (1 if width == 64 else 0)     # randint's bound must fit int64
+            raw = torch.randint(-(1 << (width - 1)), top, (m,), generator=gen, device=out.device)
+            out[lo:lo + m].view({16: torch.int16, 32: torch.int32, 64: torch.int64}[width]).copy_(raw)
             continue
         else:
             raise ValueError(kind)
@@ -86,8 +93,8 @@ def make_inputs(cfg_id, W, count, dtype, dist, device="cpu"):
 
 
 def to_wire(t):
-    """torch tensor (CPU or GPU) -> contiguous numpy wire array: float32 / int32 as is,
-    bf16 / fp16 as uint16 bit patterns."""
+    """torch tensor (CPU or GPU) -> contiguous numpy wire array: float32 / float64 / int32 /
+    int64 / uint8 as is, bf16 / fp16 as uint16 bit patterns."""
     t = t.detach().contiguous().cpu()
     if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16)
@@ -110,6 +117,8 @@ def bits_equal_nan_aware(got, want, dtype):
     eq = got == want
     if dtype == "fp32":
         eq = (got.view(np.uint32) == want.view(np.uint32)) | (np.isnan(got) & np.isnan(want))
+    elif dtype == "fp64":
+        eq = (got.view(np.uint64) == want.view(np.uint64)) | (np.isnan(got) & np.isnan(want))
     elif dtype == "bf16":
         isnan = lambda x: (x & 0x7FFF) > 0x7F80
         eq = eq | (isnan(got) & isnan(want))
