@@ -104,7 +104,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU: all W ranks are simulated in one MI355X's memory; "
+        print("bench.py: this library runs on ONE GPU: all W ranks are simulated in one MI355X's memory; "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 

@@ -141,8 +141,10 @@ typedef struct hcl_opts {
                               64..1024, multiple of 64                                        */
   int blocks;              /* workgroups per launch: 0 = default (one tile per workgroup); smaller
                               values give a persistent grid striding over the tiles            */
-  int unroll;              /* 128-bit vectors in flight per thread and source (step kernels):
-                              0 = default (2), else 1, 2, 4 or 8                              */
+  int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default (step
+                              kernels 2; FUSED All-Gather / Broadcast 1, or 4 for blocks of 1 GiB
+                              and more), else 1, 2, 4 or 8 (8: step kernels only).  The FUSED
+                              reductions always keep one vector per thread and rank           */
   int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the

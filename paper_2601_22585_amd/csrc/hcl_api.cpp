@@ -346,9 +346,17 @@ struct Ctx {
     if (nchunks > 1 && (chunk * es) % 16) al = false;
     Tuning t = tune;
     t.vec = al;
-    t.unroll = copy_mode ? 4 : fused_unroll(W);
-    // the general-form kernel (operator other than the sum, or tree order) is built for small workgroups
-    if (!copy_mode && al && (op != HCL_SUM || tree) && t.threads > kGenMaxThreads) t.threads = kGenMaxThreads;
+    // the general-form kernel (operator other than the sum, or tree order; 128-bit path only) is
+    // built for small workgroups and one vector per thread and rank
+    const bool general = !copy_mode && al && (op != HCL_SUM || tree);
+    if (copy_mode) {
+      // the caller's choice if it is one the kernel is built for, else by block size
+      const int asked = opts && opts->unroll ? opts->unroll : env_int("HCL_UNROLL", 0);
+      t.unroll = (asked == 1 || asked == 2 || asked == 4) ? asked : gather_unroll(a.B * es);
+    } else {
+      t.unroll = general ? kGenUnroll : fused_unroll(W);
+    }
+    if (general && t.threads > kGenMaxThreads) t.threads = kGenMaxThreads;
     const uint64_t tile = tile_elems(dtype, t);
     const uint64_t tpc = ceil_div(chunk, tile);
     const uint64_t total = nchunks * (uint64_t)(one_block ? 1 : W) * tpc;

@@ -7,6 +7,8 @@ namespace hcl {
 
 constexpr int kMaxSegs = 32;
 constexpr int kMaxFusedRanks = 16;
+// blocks from this size on are copied with four vectors per thread by the one-source kernel
+constexpr uint64_t kGatherBigBlock = 1ull << 30;
 
 // One rank's work in one ring step: dst0[i] (and dst1[i]) = hop(src0[i], src1[i])
 // for NSRC = 2, or = src0[i] for NSRC = 1, i in [0, n).
@@ -61,8 +63,17 @@ struct Tuning {
 
 // Elements one tile covers for this dtype / tuning (vector path or not, same figure).
 uint64_t tile_elems(int dtype, const Tuning& t);
-// 128-bit vectors per thread and source the fused kernels keep in flight for a given W.
-constexpr int fused_unroll(int W) { return W <= 4 ? 4 : (W <= 8 ? 2 : 1); }
+// 128-bit vectors per thread and rank the fused kernels keep in flight for a given W.  One
+// vector (1 KiB per wavefront and rank) measured best on MI355X for every W: against two or
+// four it gained 8-14 % at W = 2, 3, a few per cent up to W = 8, and two vectors at W = 16
+// ran into the register budget of 1024-thread workgroups.
+constexpr int fused_unroll(int /*W*/) { return 1; }
+// vectors per thread of the one-source, W-destination kernel (All-Gather, Broadcast) for a
+// block of `block_bytes`.  Measured on MI355X: one vector is 3-14 % faster than two or four up
+// to 512 MiB blocks, four vectors are 10 % faster at 2 GiB blocks.
+constexpr int gather_unroll(uint64_t block_bytes) { return block_bytes >= kGatherBigBlock ? 4 : 1; }
+// the general-form kernel (run-time operator, tree order) always keeps one
+constexpr int kGenUnroll = 1;
 
 // The general-form fused kernel keeps every rank's vector and its widened
 // elements in registers: it is built for workgroups of at most this many threads.

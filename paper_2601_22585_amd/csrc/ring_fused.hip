@@ -102,10 +102,9 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
 }
 
 // All-Gather in one launch: block c is read once from rank c and stored to all ranks.
-template <int ES, bool NT>
+template <int ES, bool NT, int U>
 __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
   constexpr uint32_t VE = 16 / ES;
-  constexpr int U = 4;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * U;
   const uint32_t W = a.W;
@@ -353,7 +352,7 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
   constexpr uint32_t VE = 16 / ES;
-  constexpr int U = fused_unroll(W);
+  constexpr int U = kGenUnroll;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * U;
   const bool to_all = a.mode == 0;
@@ -430,14 +429,22 @@ int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
   const dim3 g(t.blocks), b(t.threads);
   if (!t.vec) {
     const uint32_t es = sizeof(typename Wire<DT>::elem_t);
-    const int U = (a.mode == 2 || a.mode == 4) ? 4 : fused_unroll((int)a.W);
+    const int U = (a.mode == 2 || a.mode == 4) ? t.unroll : fused_unroll((int)a.W);
     ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U));
     return (int)hipGetLastError();
   }
   if (a.mode == 2 || a.mode == 4) {
     constexpr int ES = sizeof(typename Wire<DT>::elem_t);
-    if (t.nontemporal) gather_fused_vec<ES, true><<<g, b, 0, s>>>(a);
-    else gather_fused_vec<ES, false><<<g, b, 0, s>>>(a);
+#define HCL_CASE(UU)                                                            \
+  case UU:                                                                      \
+    if (t.nontemporal) gather_fused_vec<ES, true, UU><<<g, b, 0, s>>>(a);       \
+    else gather_fused_vec<ES, false, UU><<<g, b, 0, s>>>(a);                    \
+    break;
+    switch (t.unroll) {
+      HCL_CASE(1) HCL_CASE(2) HCL_CASE(4)
+      default: return (int)hipErrorInvalidValue;
+    }
+#undef HCL_CASE
     return (int)hipGetLastError();
   }
   constexpr bool kW = Wire<DT>::kWide;
