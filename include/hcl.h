@@ -137,12 +137,15 @@ typedef struct hcl_opts {
   size_t workspace_bytes;
   void *host_stage;        /* pinned host inboxes; see hcl_host_stage_bytes                 */
   size_t host_stage_bytes;
-  int threads;             /* threads per workgroup: 0 = default (128 stepwise, 64 fused), else
-                              64..1024, multiple of 64                                        */
+  int threads;             /* threads per workgroup: 0 = default (reducing steps 128, copying steps
+                              and the FUSED schedule 64), else 64..1024, multiple of 64; FUSED
+                              reductions with an operator other than SUM or with tree order use at
+                              most 256                                                         */
   int blocks;              /* workgroups per launch: 0 = default (one tile per workgroup); smaller
                               values give a persistent grid striding over the tiles            */
-  int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default (step
-                              kernels 2; FUSED All-Gather / Broadcast 1, or 4 for blocks of 1 GiB
+  int unroll;              /* 128-bit vectors in flight per thread and source: 0 = default (reducing
+                              steps 2, copying steps 1 -- when threads is 0 too; FUSED All-Gather /
+                              Broadcast 1, or 4 for blocks of 1 GiB
                               and more), else 1, 2, 4 or 8 (8: step kernels only).  The FUSED
                               reductions always keep one vector per thread and rank           */
   int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
