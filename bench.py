@@ -81,7 +81,8 @@ def parse():
     ap.add_argument("--order", default="ring", choices=["ring", "tree"],
                     help="tree: fused reductions over a neighbours-first tree (a reordered-class result)")
     ap.add_argument("--inplace", action="store_true")
-    ap.add_argument("--bytes-per-rank", type=int, default=0, help="config 3: bytes per rank buffer")
+    ap.add_argument("--bytes-per-rank", type=int, default=0,
+                    help="config 3: bytes per rank buffer; configs 1, 2, 5: the same workload at this size")
     ap.add_argument("--shard-elems", type=int, default=0, help="config 4: elements per shard (default 2 GiB worth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=1 << 24,
@@ -139,6 +140,10 @@ def main():
     else:
         count = cfg["count"]
         chunk_default = cfg["chunk_bytes"]
+        if args.bytes_per_rank:          # the same workload family at another message size
+            count = args.bytes_per_rank // es
+            name = f"{name}_resized_{args.bytes_per_rank}B"
+            chunk_default = min(-(-count // W) * es, cfg["chunk_bytes"])
     chunk_bytes = chunk_default if args.chunk_bytes < 0 else args.chunk_bytes
     S = count * es                 # bytes of a full vector (per rank)
     B = -(-count // W)             # elements per block
