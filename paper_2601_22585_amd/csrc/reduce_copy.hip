@@ -108,39 +108,45 @@ uint64_t tile_elems(int dtype, const Tuning& t) {
   return (uint64_t)t.threads * (16 / es) * t.unroll;
 }
 
-template <int DT, int NSRC, int NDST>
-static int launch_step_t(const StepArgs& a, const Tuning& t, hipStream_t s) {
+// GEN: the kernel reads the operator from the step's arguments (anything but the sum)
+template <int DT, int NSRC, int NDST, bool GEN>
+static int launch_step_vec(const StepArgs& a, const Tuning& t, hipStream_t s) {
   const dim3 g(t.blocks), b(t.threads);
-  if (!t.vec) {
-    reduce_copy_elem<DT, NSRC, NDST><<<g, b, 0, s>>>(a, (uint32_t)tile_elems(DT, t));
-    return (int)hipGetLastError();
-  }
 #define HCL_CASE(U)                                                                          \
   case U:                                                                                    \
     if (t.nontemporal) reduce_copy_vec<DT, NSRC, NDST, U, true, GEN><<<g, b, 0, s>>>(a);     \
     else reduce_copy_vec<DT, NSRC, NDST, U, false, GEN><<<g, b, 0, s>>>(a);                  \
     break;
-  if (NSRC == 2 && a.op != OP_SUM) {
-    constexpr bool GEN = NSRC == 2;
-    switch (t.unroll) {
-      HCL_CASE(1) HCL_CASE(2) HCL_CASE(4) HCL_CASE(8)
-      default: return (int)hipErrorInvalidValue;
-    }
-  } else {
-    constexpr bool GEN = false;
-    switch (t.unroll) {
-      HCL_CASE(1) HCL_CASE(2) HCL_CASE(4) HCL_CASE(8)
-      default: return (int)hipErrorInvalidValue;
-    }
+  switch (t.unroll) {
+    HCL_CASE(1) HCL_CASE(2) HCL_CASE(4) HCL_CASE(8)
+    default: return (int)hipErrorInvalidValue;
   }
 #undef HCL_CASE
   return (int)hipGetLastError();
 }
 
+template <int DT, int NSRC, int NDST>
+static int launch_step_t(const StepArgs& a, const Tuning& t, hipStream_t s) {
+  if (!t.vec) {
+    reduce_copy_elem<DT, NSRC, NDST><<<dim3(t.blocks), dim3(t.threads), 0, s>>>(a, (uint32_t)tile_elems(DT, t));
+    return (int)hipGetLastError();
+  }
+  if constexpr (NSRC == 2) {
+    if (a.op != OP_SUM) return launch_step_vec<DT, NSRC, NDST, true>(a, t, s);
+  }
+  return launch_step_vec<DT, NSRC, NDST, false>(a, t, s);
+}
+
+// A copy moves bits: only one wire type per element size carries the NSRC = 1 kernels.
+template <int DT>
+constexpr bool kCopyType = DT == DT_UINT8 || DT == DT_BF16 || DT == DT_INT32 || DT == DT_INT64;
+
 template <int DT>
 static int launch_step_d(const StepArgs& a, int nsrc, int ndst, const Tuning& t, hipStream_t s) {
-  if (nsrc == 1 && ndst == 1) return launch_step_t<DT, 1, 1>(a, t, s);
-  if (nsrc == 1 && ndst == 2) return launch_step_t<DT, 1, 2>(a, t, s);
+  if constexpr (kCopyType<DT>) {
+    if (nsrc == 1 && ndst == 1) return launch_step_t<DT, 1, 1>(a, t, s);
+    if (nsrc == 1 && ndst == 2) return launch_step_t<DT, 1, 2>(a, t, s);
+  }
   if (nsrc == 2 && ndst == 1) return launch_step_t<DT, 2, 1>(a, t, s);
   if (nsrc == 2 && ndst == 2) return launch_step_t<DT, 2, 2>(a, t, s);
   return (int)hipErrorInvalidValue;
@@ -148,7 +154,7 @@ static int launch_step_d(const StepArgs& a, int nsrc, int ndst, const Tuning& t,
 
 int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& t, void* stream) {
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  // a copy moves bits: share the integer instantiations of the same element size
+  // a copy moves bits: route it to the wire type that carries the copy kernels of this element size
   if (nsrc == 1) {
     switch (elem_size(dtype)) {
       case 1: dtype = DT_UINT8; break;
@@ -168,7 +174,6 @@ int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& 
   }
   return (int)hipErrorInvalidValue;
 }
-
 
 // FUSED: the kernels of each wire type live in object files of their own
 int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream) {

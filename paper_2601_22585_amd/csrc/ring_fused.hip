@@ -14,7 +14,6 @@
 
 namespace hcl {
 
-
 #if HCL_FUSED_PART == 0
 // ---------------------------------------------------------------------------
 // FUSED: the whole ring pass of an element inside one thread.
@@ -22,7 +21,6 @@ namespace hcl {
 // to the wire type after every addition -- the value the stepwise ring
 // produces, with each rank's element read once.
 // ---------------------------------------------------------------------------
-
 template <int DT, int W, bool NT, bool WIDE>
 __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
   typedef typename Wire<DT>::elem_t elem_t;

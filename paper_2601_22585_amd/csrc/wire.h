@@ -15,7 +15,6 @@
 
 namespace hcl {
 
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 enum { DT_FP32 = 0, DT_BF16 = 1, DT_FP16 = 2, DT_INT32 = 3, DT_FP64 = 4, DT_INT64 = 5, DT_UINT8 = 6 };
