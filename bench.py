@@ -51,11 +51,12 @@ def stored_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 counter runs, or None
     when there are none for this kernel / workload or the kernel source has
     changed since they were taken."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    path = os.path.join(ROOT, "profiles", "traffic.md")
     if not os.path.exists(path):
         return None
     try:
-        rec = json.load(open(path))
+        text = open(path).read()
+        rec = json.loads(text.split("```json", 1)[1].split("```", 1)[0])
     except Exception:
         return None
     for e in rec.get("entries", []):
