@@ -264,7 +264,6 @@ struct Ctx {
     tune.threads = threads;
     tune.unroll = unroll;
     tune.nontemporal = nt >= 0;
-    tune.vec = true;
     max_blocks = blocks;  // 0 = decide at launch from the CU count
     return HCL_OK;
   }
@@ -304,20 +303,11 @@ struct Ctx {
   hcl_status_t launch(StepArgs& a, int nsrc, int ndst) {
     if (a.nseg == 0) return HCL_OK;
     uint64_t maxn = 0;
-    bool al = true;
-    for (uint32_t i = 0; i < a.nseg; ++i) {
-      const Seg& s = a.seg[i];
-      if (s.n > maxn) maxn = s.n;
-      uintptr_t bits = (uintptr_t)s.src0 | (uintptr_t)s.dst0;
-      if (nsrc == 2) bits |= (uintptr_t)s.src1;
-      if (ndst == 2) bits |= (uintptr_t)s.dst1;
-      if (bits & 15) al = false;
-    }
+    for (uint32_t i = 0; i < a.nseg; ++i)
+      if (a.seg[i].n > maxn) maxn = a.seg[i].n;
     uint64_t chunk = (chunk_elems && chunk_elems < maxn) ? chunk_elems : maxn;
     const uint64_t nchunks = ceil_div(maxn, chunk);
-    if (nchunks > 1 && (chunk * es) % 16) al = false;
     Tuning t = tune;
-    t.vec = al;
     // defaults from sweeps on MI355X: reducing steps 128 threads x 2 vectors per source (4 KiB per
     // source and workgroup), copying steps one wavefront x 1 vector (3 % faster for them)
     if (nsrc == 1 && auto_threads && auto_unroll) {
@@ -346,17 +336,12 @@ struct Ctx {
     if (a.count == 0) return HCL_OK;
     const bool one_block = a.mode >= 3;  // Reduce / Broadcast
     const bool copy_mode = a.mode == 2 || a.mode == 4;
-    bool al = one_block || (a.B * es) % 16 == 0;
-    for (int r = 0; r < W; ++r)
-      if (((uintptr_t)a.src[r] | (uintptr_t)a.dst[r]) & 15) al = false;
     uint64_t chunk = (chunk_elems && chunk_elems < a.B) ? chunk_elems : a.B;
     const uint64_t nchunks = ceil_div(a.B, chunk);
-    if (nchunks > 1 && (chunk * es) % 16) al = false;
     Tuning t = tune;
-    t.vec = al;
-    // the general-form kernel (operator other than the sum, or tree order; 128-bit path only) is
+    // the general-form kernel (operator other than the sum, or tree order) is
     // built for small workgroups and one vector per thread and rank
-    const bool general = !copy_mode && al && (op != HCL_SUM || tree);
+    const bool general = !copy_mode && (op != HCL_SUM || tree);
     if (copy_mode) {
       // the caller's choice if it is one the kernel is built for, else by block size
       const int asked = opts && opts->unroll ? opts->unroll : env_int("HCL_UNROLL", 0);

@@ -58,10 +58,9 @@ struct Tuning {
   int blocks;       // workgroups
   int unroll;       // 1, 2, 4, 8
   bool nontemporal;
-  bool vec;         // 128-bit path allowed (all addresses 16-byte aligned)
 };
 
-// Elements one tile covers for this dtype / tuning (vector path or not, same figure).
+// Elements one tile covers for this dtype / tuning.
 uint64_t tile_elems(int dtype, const Tuning& t);
 // 128-bit vectors per thread and rank the fused kernels keep in flight for a given W.  One
 // vector (1 KiB per wavefront and rank) measured best on MI355X for every W: against two or
@@ -84,7 +83,7 @@ int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& 
 int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream);
 
 // Per wire type (0 fp32, 1 bf16, 2 fp16, 3 int32, 4 fp64, 5 int64, 6 uint8), one object file each:
-// ring-order sums, copies and the element-wise path / the general form.
+// ring-order sums and copies / the general form.
 template <int DT> int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream);
 template <int DT> int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream);
 

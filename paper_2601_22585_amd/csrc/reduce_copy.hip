@@ -78,28 +78,6 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
   }
 }
 
-// Element-wise path for addresses that are not 16-byte aligned.  Same tiles.
-template <int DT, int NSRC, int NDST>
-__global__ void __launch_bounds__(1024) reduce_copy_elem(const StepArgs a, const uint32_t tile) {
-  typedef typename Wire<DT>::elem_t elem_t;
-  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
-  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile, a.stagger);
-    const uint32_t len = tile_len(p, a.seg[p.d].n, a.chunk, tile);
-    if (len == 0) continue;
-    const elem_t* s0 = reinterpret_cast<const elem_t*>(a.seg[p.d].src0) + p.lo;
-    const elem_t* s1 = NSRC == 2 ? reinterpret_cast<const elem_t*>(a.seg[p.d].src1) + p.lo : nullptr;
-    elem_t* d0 = reinterpret_cast<elem_t*>(a.seg[p.d].dst0) + p.lo;
-    elem_t* d1 = NDST == 2 ? reinterpret_cast<elem_t*>(a.seg[p.d].dst1) + p.lo : nullptr;
-    for (uint32_t e = tid; e < len; e += nthr) {
-      elem_t r = s0[e];
-      if (NSRC == 2) r = a.op ? op_elem<DT>(a.op, r, s1[e]) : Wire<DT>::hop_elem(r, s1[e]);
-      d0[e] = r;
-      if (NDST == 2) d1[e] = r;
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------
 // host-side dispatch
 // ---------------------------------------------------------------------------
@@ -127,10 +105,6 @@ static int launch_step_vec(const StepArgs& a, const Tuning& t, hipStream_t s) {
 
 template <int DT, int NSRC, int NDST>
 static int launch_step_t(const StepArgs& a, const Tuning& t, hipStream_t s) {
-  if (!t.vec) {
-    reduce_copy_elem<DT, NSRC, NDST><<<dim3(t.blocks), dim3(t.threads), 0, s>>>(a, (uint32_t)tile_elems(DT, t));
-    return (int)hipGetLastError();
-  }
   if constexpr (NSRC == 2) {
     if (a.op != OP_SUM) return launch_step_vec<DT, NSRC, NDST, true>(a, t, s);
   }
@@ -178,7 +152,7 @@ int launch_step(const StepArgs& a, int dtype, int nsrc, int ndst, const Tuning& 
 // FUSED: the kernels of each wire type live in object files of their own
 int launch_fused(const FusedArgs& a, int dtype, const Tuning& t, void* stream) {
   const bool copy = a.mode == 2 || a.mode == 4;
-  const bool gen = !copy && t.vec && (a.op != OP_SUM || a.tree);
+  const bool gen = !copy && (a.op != OP_SUM || a.tree);
   switch (dtype) {
     case DT_FP32: return gen ? launch_fused_gen<DT_FP32>(a, t, stream) : launch_fused_sum<DT_FP32>(a, t, stream);
     case DT_BF16: return gen ? launch_fused_gen<DT_BF16>(a, t, stream) : launch_fused_sum<DT_BF16>(a, t, stream);

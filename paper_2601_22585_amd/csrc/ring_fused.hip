@@ -2,8 +2,8 @@
 // stays inside one thread, every rank's value is read once.
 //
 // This file is compiled once per (HCL_FUSED_DT, HCL_FUSED_PART): the wire type
-// (0 fp32, 1 bf16, 2 fp16, 3 int32, 4 fp64, 5 int64, 6 uint8) and the part -- 0: ring-order sums, the
-// All-Gather / Broadcast kernel and the element-wise path; 1: the general form
+// (0 fp32, 1 bf16, 2 fp16, 3 int32, 4 fp64, 5 int64, 6 uint8) and the part -- 0: ring-order sums and the
+// All-Gather / Broadcast kernel; 1: the general form
 // (run-time operator, tree order, rounding once).  Each object file holds one
 // explicit instantiation of launch_fused_sum<DT> or launch_fused_gen<DT>.
 #include "wire.h"
@@ -144,81 +144,6 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
       } else {
         const uint64_t x = reinterpret_cast<const uint64_t*>(s)[e];
         for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint64_t*>(a.dst[r] + voff)[e] = x;
-      }
-    }
-  }
-}
-
-// Element-wise fused path (any alignment, any W, every mode, operator, order and rounding).
-template <int DT>
-__global__ void __launch_bounds__(1024) ring_fused_elem(const FusedArgs a, const uint32_t tile) {
-  typedef typename Wire<DT>::elem_t elem_t;
-  const uint32_t tid = threadIdx.x, nthr = blockDim.x;
-  const uint32_t W = a.W;
-  const bool whole = a.mode >= 3;  // Reduce / Broadcast: one block, the whole vector, owned by the root
-  const bool one_src = a.mode == 2 || a.mode == 4;
-  const bool one_dst = a.mode == 1 || a.mode == 3;
-  const uint32_t op = a.op;
-  const bool tree = a.tree != 0;
-  const bool wide = Wire<DT>::kWide && a.wide != 0;
-  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
-    const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
-    const uint32_t c = whole ? a.root : p.d;
-    uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
-    if (blo > a.count) blo = a.count;
-    if (bhi > a.count) bhi = a.count;
-    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
-    if (len == 0) continue;
-    const uint32_t first = tree ? 0u : a.pos[c] + 1u;
-    for (uint32_t e = tid; e < len; e += nthr) {
-      const uint64_t i = p.lo + e;  // inside block c
-      elem_t acc;
-      if (one_src) {
-        acc = reinterpret_cast<const elem_t*>(a.src[c])[i];
-      } else if (DT == DT_INT32 || DT == DT_INT64 || DT == DT_UINT8 || DT == DT_FP64) {
-        // integers: 64-bit values, sign- or zero-extended, truncated to the element at the end;
-        // fp64: its bit pattern
-        uint64_t v[kMaxFusedRanks];
-        for (uint32_t k = 0; k < W; ++k) {
-          const elem_t x = reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
-          v[k] = DT == DT_INT32 ? (uint64_t)(int64_t)(int32_t)x : (uint64_t)x;
-        }
-        auto node = [&](uint64_t x, uint64_t y) { return op_elem64<DT == DT_FP64 ? DT_FP64 : DT_INT64>(op, x, y); };
-        if (!tree) {
-          for (uint32_t k = 1; k < W; ++k) v[0] = node(v[0], v[k]);
-        } else {
-          for (uint32_t n = W; n > 1; n = (n + 1) / 2) {
-            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = node(v[k], v[k + 1]);
-            if (n & 1) v[n / 2] = v[n - 1];
-          }
-        }
-        acc = (elem_t)v[0];
-      } else {
-        float v[kMaxFusedRanks];
-        for (uint32_t k = 0; k < W; ++k) {
-          const elem_t x = reinterpret_cast<const elem_t*>(a.src[a.order[(first + k) % W]])[blo + i];
-          v[k] = Wire<DT>::kWide ? widen1<DT>(x) : u2f((uint32_t)x);
-        }
-        // one node: the operator, then (unless wide) a trip through the wire type
-        auto node = [&](float x, float y) {
-          float r = apply_f32(op, x, y);
-          if (Wire<DT>::kWide && !wide) r = widen1<DT>(narrow1<DT>(r));
-          return r;
-        };
-        if (!tree) {
-          for (uint32_t k = 1; k < W; ++k) v[0] = node(v[0], v[k]);
-        } else {
-          for (uint32_t n = W; n > 1; n = (n + 1) / 2) {
-            for (uint32_t k = 0; k + 1 < n; k += 2) v[k / 2] = node(v[k], v[k + 1]);
-            if (n & 1) v[n / 2] = v[n - 1];
-          }
-        }
-        acc = Wire<DT>::kWide ? narrow1<DT>(v[0]) : (elem_t)f2u(v[0]);
-      }
-      if (one_dst) {
-        reinterpret_cast<elem_t*>(a.dst[c])[i] = acc;
-      } else {
-        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r])[blo + i] = acc;
       }
     }
   }
@@ -425,12 +350,6 @@ template <int DT>
 int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const dim3 g(t.blocks), b(t.threads);
-  if (!t.vec) {
-    const uint32_t es = sizeof(typename Wire<DT>::elem_t);
-    const int U = (a.mode == 2 || a.mode == 4) ? t.unroll : fused_unroll((int)a.W);
-    ring_fused_elem<DT><<<g, b, 0, s>>>(a, (uint32_t)(t.threads * (16 / es) * U));
-    return (int)hipGetLastError();
-  }
   if (a.mode == 2 || a.mode == 4) {
     constexpr int ES = sizeof(typename Wire<DT>::elem_t);
 #define HCL_CASE(UU)                                                            \

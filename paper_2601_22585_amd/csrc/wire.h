@@ -22,15 +22,18 @@ enum { DT_FP32 = 0, DT_BF16 = 1, DT_FP16 = 2, DT_INT32 = 3, DT_FP64 = 4, DT_INT6
 // ---------------------------------------------------------------------------
 // memory access helpers
 // ---------------------------------------------------------------------------
+// 128-bit accesses that promise no alignment beyond one byte: the instruction is the same
+// global_load_dwordx4 / global_store_dwordx4, and the hardware serves any address
+typedef u32x4 u32x4_any __attribute__((aligned(1)));
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(const char* p) {
-  const u32x4* q = reinterpret_cast<const u32x4*>(p);
+  const u32x4_any* q = reinterpret_cast<const u32x4_any*>(p);
   if (NT) return __builtin_nontemporal_load(q);
   return *q;
 }
 template <bool NT>
 __device__ __forceinline__ void st16(char* p, u32x4 v) {
-  u32x4* q = reinterpret_cast<u32x4*>(p);
+  u32x4_any* q = reinterpret_cast<u32x4_any*>(p);
   if (NT) __builtin_nontemporal_store(v, q);
   else *q = v;
 }

@@ -47,7 +47,7 @@ def test_allreduce_ragged_sizes_rings_chunks(dtype, sched):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-def test_allreduce_misaligned_buffers_take_the_elementwise_path(dtype):
+def test_allreduce_buffers_aligned_to_the_element_size_only(dtype):
     for sched in ("stepwise", "fused"):
         for mis in (1, 3):
             run_allreduce(120, 4, 50_001, dtype, DIST[dtype], chunk_bytes=0, misalign=mis, sched=sched)
