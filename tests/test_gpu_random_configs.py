@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import CODE, assert_same_bits, device_inputs, fresh
+from gpu_util import (CODE, assert_same_bits, device_inputs, fresh, run_all_gather, run_alltoall, run_broadcast)
 from oracle import ring_oracle as orc
 from paper_2601_22585_amd import hcl
 
@@ -93,6 +93,29 @@ def _run(c, seed):
         hcl.reduce_sim(dev, out, root, **opt)
         torch.cuda.synchronize()
         assert_same_bits(out[root], want, dtype, tag)
+
+
+@pytest.mark.parametrize("batch", range(3))
+def test_random_configurations_of_the_copying_collectives(batch):
+    rnd = random.Random(30260 + batch)
+    for i in range(40):
+        seed = 7000 + 100 * batch + i
+        dtype = rnd.choice(list(DIST))
+        es = wl.ESIZE[dtype]
+        W = rnd.choice([1, 2, 3, 5, 8, 13, 16])
+        n = rnd.choice([1, 17, 4096, rnd.randrange(1, 60_000)])
+        opt = dict(ring=None if rnd.random() < 0.4 else rnd.sample(range(W), W),
+                   chunk_bytes=rnd.choice([0, 0, 1, 64, 4096, rnd.randrange(1, 20_000)]) * es,
+                   misalign=rnd.choice([0, 0, 1, 3]), sched=rnd.choice(["stepwise", "fused"]),
+                   threads=rnd.choice([0, 0, 64, 256]), unroll=rnd.choice([0, 0, 1, 2, 4]),
+                   blocks=rnd.choice([0, 0, 5, 300]))
+        kind = rnd.choice(["all_gather", "broadcast", "alltoall"])
+        if kind == "all_gather":
+            run_all_gather(seed, W, n, dtype, DIST[dtype], inplace=rnd.random() < 0.3 and opt["misalign"] == 0, **opt)
+        elif kind == "broadcast":
+            run_broadcast(seed, W, n, dtype, DIST[dtype], seed % W, inplace=rnd.random() < 0.3, **opt)
+        else:
+            run_alltoall(seed, W, n, dtype, DIST[dtype], **opt)
 
 
 @pytest.mark.parametrize("batch", range(6))
