@@ -68,9 +68,17 @@
  * tests/golden/; W = 2 against numpy / torch elementwise adds; integer-valued
  * inputs against exact integer sums; conversions against numpy float16 and
  * torch bfloat16 over all 2^16 patterns and sampled fp32 patterns; set-based
- * simulation of the block tables for every W <= 16.  The paper prints no value
- * for this path, so parity against the paper itself is unpinned; every pin is
- * derived from the arithmetic.
+ * simulation of the block tables for every W <= 16.  Operators, tree order and
+ * single rounding: exact-rational brute force of every combination; the
+ * hand-derived overflow / underflow product example and the tree-order
+ * cancellation example under tests/golden/; IEEE 754-2019 maximum / minimum of
+ * special operands written out there; two ranks against numpy / torch multiply,
+ * maximum, minimum on random bit patterns; order independence of maximum /
+ * minimum and of the integer types; the pairwise-summation and 2-ulp bounds.
+ * fp64 / int64 / uint8: the same brute force at binary64 width and in big
+ * integers with explicit wrap.  The paper prints no value for this path, so
+ * parity against the paper itself is unpinned; every pin is derived from the
+ * arithmetic.
  *
  * Build: gcc -O2 -std=c11 -fopenmp -ffp-contract=off -fPIC -shared
  */
