@@ -41,11 +41,11 @@
  *     has; buffers that are not 16-byte aligned (or not congruent modulo 128
  *     bytes with each other) make accesses straddle cache lines and measured
  *     10-25 % slower on MI355X than 256-byte aligned ones.
- *   - Layout advice: rank buffers whose addresses are all congruent modulo a
- *     large power of two (say, every buffer 2 GiB-aligned) make the streams of
- *     a step fall into the same DRAM banks; starting successive buffers
- *     64 KiB + 256 B further into their allocations was worth up to 7 % on
- *     MI355X.  The library skews its own workspace and inbox slots that way.
+ *   - Layout advice: give every rank buffer an allocation of its own (or pack
+ *     them back to back) with at least 256-byte alignment.  The kernels walk the
+ *     ranks' streams at staggered offsets, so equally aligned buffers do not
+ *     collide in DRAM; offsetting the buffers against each other by odd amounts
+ *     (64 KiB + 256 B, say) measured 3-7 % slower on MI355X.
  *   - Launch-shape fields of hcl_opts_t that are 0 may be overridden by the
  *     environment variables HCL_THREADS, HCL_UNROLL, HCL_BLOCKS and
  *     HCL_NONTEMPORAL (for sweeps); values in the struct win.
@@ -261,14 +261,13 @@ hcl_status_t hcl_alltoall_sim(const void *const *send, void *const *recv, int W,
  * (0 for everything except a STEPWISE Reduce with W > 2 -- two slots of the
  * vector -- and an out-of-place STEPWISE Reduce-Scatter with W > 2,
  * where the caller cannot say "in place" here: the figure is the out-of-place
- * one: 2 * W slots of one block rounded up to 256 bytes plus a 64 KiB + 256 B
- * skew).  `count` is the per-call count argument of that entry point.  Returns
+ * one: 2 * W slots of one block rounded up to 256 bytes).  `count` is the per-call count argument of that entry point.  Returns
  * 0 on invalid arguments too. */
 size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                            const hcl_opts_t *opts);
 
 /* Pinned host memory the HOST_STAGED transport needs in opts->host_stage:
- * two inbox slots (sized like the workspace slots) of one block per rank.  0 for the DIRECT transport. */
+ * two inbox slots (one block rounded up to 256 bytes each) per rank.  0 for the DIRECT transport. */
 size_t hcl_host_stage_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                             const hcl_opts_t *opts);
 

@@ -112,8 +112,8 @@ def test_staging_and_workspace_rules():
 
 def test_workspace_and_host_stage_sizes():
     # out-of-place stepwise reduce-scatter: two slots per rank, each one block rounded up to
-    # 256 bytes plus the 64 KiB + 256 B skew between slots
-    skew = 65536 + 256
+    # 256 bytes
+    skew = 0
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * 2 * ((1 << 21) + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * 2 * (512 + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 2, 1 << 20, hcl.BF16) == 0
@@ -212,6 +212,6 @@ def test_other_collectives_validation_codes():
     assert L.hcl_alltoall_sim(ps, ps, 4, 16, hcl.FP32, 0, ctypes.byref(o), None) == hcl.ERR_ALIAS
     pr_null = (ctypes.c_void_p * 4)(None, r[1], r[2], r[3])
     assert L.hcl_reduce_sim(ps, pr_null, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * ((1 << 21) + 65536 + 256)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * (1 << 21)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16, sched="fused") == 0
     assert hcl.workspace_bytes(hcl.KIND_BROADCAST, 8, 1 << 20, hcl.BF16) == 0
