@@ -10,14 +10,38 @@ from paper_2601_22585_amd import hcl
 CODE = wl.DTYPE_CODE
 
 
+PAD = 256          # guard elements before and after every buffer the helpers allocate
+GUARD_BYTE = 0xA5
+_guarded = []      # (allocation, first data element, data elements) since the last check
+
+
+def guarded(count, torch_dtype, misalign=0):
+    """A `count`-element device buffer `misalign` elements past a 256-byte aligned address,
+    with PAD guard elements on either side that check_guards() expects to find untouched."""
+    base = torch.empty(PAD + misalign + count + PAD, dtype=torch_dtype, device="cuda")
+    base.view(torch.uint8).fill_(GUARD_BYTE)
+    _guarded.append((base, PAD + misalign, count))
+    return base[PAD + misalign:PAD + misalign + count]
+
+
+def check_guards():
+    """No kernel may have written outside the buffers it was given (scalar tails, vectors that
+    straddle the end of a misaligned buffer): every guard byte must still hold its pattern."""
+    torch.cuda.synchronize()
+    for base, lo, count in _guarded:
+        b, es = base.view(torch.uint8), base.element_size()
+        assert bool((b[:lo * es] == GUARD_BYTE).all()), "bytes before a buffer were overwritten"
+        assert bool((b[(lo + count) * es:] == GUARD_BYTE).all()), "bytes after a buffer were overwritten"
+    _guarded.clear()
+
+
 def device_inputs(cfg_id, W, count, dtype, dist, misalign=0):
     """CPU-generated seeded inputs and their device copies.  misalign > 0 places
-    every device buffer `misalign` elements past a 256-byte aligned allocation."""
+    every device buffer `misalign` elements past a 256-byte aligned address."""
     cpu = wl.make_inputs(cfg_id, W, count, dtype, dist)
     dev = []
     for t in cpu:
-        base = torch.empty(count + misalign + 64, dtype=t.dtype, device="cuda")
-        d = base[misalign:misalign + count]
+        d = guarded(count, t.dtype, misalign)
         d.copy_(t)
         dev.append(d)
     return cpu, dev
@@ -26,8 +50,7 @@ def device_inputs(cfg_id, W, count, dtype, dist, misalign=0):
 def fresh(W, count, dtype, misalign=0, fill=None):
     out = []
     for _ in range(W):
-        base = torch.empty(count + misalign + 64, dtype=wl.TORCH_DTYPE[dtype], device="cuda")
-        d = base[misalign:misalign + count]
+        d = guarded(count, wl.TORCH_DTYPE[dtype], misalign)
         if fill is not None:
             d.fill_(fill)
         out.append(d)
@@ -55,12 +78,7 @@ def run_allreduce(cfg_id, W, count, dtype, dist, ring=None, chunk_bytes=0, inpla
         cpu, dev = device_inputs(cfg_id, W, count, dtype, dist, misalign)
     else:
         cpu = cpu_inputs
-        dev = []
-        for t in cpu:
-            base = torch.empty(count + misalign + 64, dtype=t.dtype, device="cuda")
-            d = base[misalign:misalign + count]
-            d.copy_(t)
-            dev.append(d)
+        dev = [_to_dev(t, misalign) for t in cpu]
     es = wl.ESIZE[dtype]
     want = orc.allreduce([wl.to_wire(t) for t in cpu], CODE[dtype], ring=ring,
                          chunk_elems=chunk_bytes // es)
@@ -75,6 +93,7 @@ def run_allreduce(cfg_id, W, count, dtype, dist, ring=None, chunk_bytes=0, inpla
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
         if not inplace:
             assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    check_guards()
     return n
 
 
@@ -100,6 +119,7 @@ def run_reduce_scatter(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, inpl
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
         if not inplace:
             assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    check_guards()
     return nl
 
 
@@ -116,23 +136,18 @@ def run_all_gather(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, inplace=
         for r in range(W):
             send[r].copy_(cpu[r])
     else:
-        send = []
-        for t in cpu:
-            base = torch.empty(n + misalign + 64, dtype=t.dtype, device="cuda")
-            d = base[misalign:misalign + n]
-            d.copy_(t)
-            send.append(d)
+        send = [_to_dev(t, misalign) for t in cpu]
     nl = hcl.all_gather_sim(send, recv, chunk_bytes=chunk_bytes, ring=ring, **opt)
     torch.cuda.synchronize()
     tag = f"all_gather W={W} n={n} {dtype} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')} {opt.get('xport')}"
     for r in range(W):
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+    check_guards()
     return nl
 
 
 def _to_dev(t, misalign=0):
-    base = torch.empty(t.numel() + misalign + 64, dtype=t.dtype, device="cuda")
-    d = base[misalign:misalign + t.numel()]
+    d = guarded(t.numel(), t.dtype, misalign)
     d.copy_(t)
     return d
 
@@ -153,6 +168,7 @@ def run_reduce(cfg_id, W, count, dtype, dist, root, ring=None, chunk_bytes=0, in
     for r in range(W):
         if not (inplace and r == root):
             assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    check_guards()
     return n
 
 
@@ -171,6 +187,7 @@ def run_broadcast(cfg_id, W, count, dtype, dist, root, ring=None, chunk_bytes=0,
     tag = f"broadcast W={W} count={count} {dtype} root={root} ring={ring} chunk={chunk_bytes} inplace={inplace} mis={misalign} {opt.get('sched')}"
     for r in range(W):
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
+    check_guards()
     return n
 
 
@@ -185,4 +202,5 @@ def run_alltoall(cfg_id, W, n, dtype, dist, ring=None, chunk_bytes=0, misalign=0
     for r in range(W):
         assert_same_bits(recv[r], want[r], dtype, f"{tag} rank {r}")
         assert_same_bits(dev[r], wl.to_wire(cpu[r]), dtype, f"{tag} send[{r}] must stay untouched")
+    check_guards()
     return nl

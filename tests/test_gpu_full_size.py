@@ -91,39 +91,132 @@ def test_config3_one_gib_per_rank_windows():
             assert torch.equal(recv[r].view(torch.int16), recv[0].view(torch.int16))
 
 
+def _view_int(t):
+    return t.view({1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[t.element_size()])
+
+
+def _fill_all(send, cfg_id, dist):
+    for r, t in enumerate(send):
+        wl.fill_rank(t, wl.rank_seed(cfg_id, r), dist)
+
+
 @pytest.mark.parametrize("cfg_id", [4, 41])
-def test_config4_reduce_scatter_then_all_gather_windows(cfg_id):
-    """Shards of 2^27 elements (one eighth of the named 2 GiB shards, so that this
-    test stays within a minute; bench.py runs the named size), out of place with
-    workspace, then All-Gather of the shards; oracle on windows."""
+def test_config4_named_size_reduce_scatter_then_all_gather(cfg_id):
+    """The ZeRO-style split operations at their named size: W = 8 ranks, 2 GiB shards
+    (2^30 bf16 / 2^29 int32 elements), 16 GiB per rank buffer, so that byte offsets inside
+    a buffer reach 2^34 and blocks are 2 GiB long.  Reduce-Scatter: STEPWISE out of place
+    (workspace), FUSED, STEPWISE in place, FUSED in place; All-Gather: STEPWISE, FUSED,
+    STEPWISE in place.  The oracle replays windows: the first and the last 2^16 elements
+    of every block of every rank (the very end of the 16 GiB buffers included), a window
+    across a chunk boundary and a seeded interior one; every other comparison is a whole
+    2 GiB block against another on the device."""
     c = wl.CONFIGS[cfg_id]
-    W, dtype = c["W"], c["dtype"]
+    W, dtype, chunk = c["W"], c["dtype"], c["chunk_bytes"]
     es = wl.ESIZE[dtype]
-    n = (1 << 28) // es                    # 256 MiB shards
-    count = n * W
-    send = _device_inputs(cfg_id, W, count, dtype, c["dist"])
-    shard = [torch.zeros(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
-    ws = torch.empty(hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device="cuda")
-    hcl.reduce_scatter_sim(send, shard, chunk_bytes=c["chunk_bytes"], workspace=ws)
-    torch.cuda.synchronize()
+    code = wl.DTYPE_CODE[dtype]
+    n = c["count"] // W
+    assert n * es == 2 << 30 and n * W * es == 16 << 30
+    send = [torch.empty(n * W, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
+    _fill_all(send, cfg_id, c["dist"])
     m = 1 << 16
-    for off in (0, n - m, (4 << 20) // es - m // 2, 7654321 // es * es):
+    rnd = np.random.default_rng(4100 + cfg_id)
+    offs = [0, n - m, chunk // es - m // 2, int(rnd.integers(0, n - m))]
+    want = {}
+    for off in offs:
         ins = [np.concatenate([wl.to_wire(send[r][q * n + off:q * n + off + m]) for q in range(W)]) for r in range(W)]
-        want = orc.reduce_scatter(ins, wl.DTYPE_CODE[dtype])
-        for r in range(W):
-            assert np.array_equal(wl.to_wire(shard[r][off:off + m]), want[r]), (off, r)
+        want[off] = orc.reduce_scatter(ins, code)
+
+    def check_shards(shard, what):
+        for off in offs:
+            for r in range(W):
+                assert np.array_equal(wl.to_wire(shard[r][off:off + m]), want[off][r]), (what, off, r)
+
+    # --- Reduce-Scatter, out of place: STEPWISE with workspace, then FUSED ---
+    ws = torch.empty(hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, code, chunk), dtype=torch.uint8, device="cuda")
+    shard = [torch.zeros(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
+    assert hcl.reduce_scatter_sim(send, shard, chunk_bytes=chunk, workspace=ws) == W - 1
+    torch.cuda.synchronize()
+    del ws
+    check_shards(shard, "stepwise out of place")
     if dtype == "int32":
         # exact and order-free: the whole result equals the plain integer sum
         for r in range(W):
             tot = torch.zeros(n, dtype=torch.int64, device="cuda")
             for q in range(W):
                 tot += send[q][r * n:(r + 1) * n]
-            assert torch.equal(tot.to(torch.int32), shard[r])
-    del ws
-    full = send                             # reuse the inputs' memory for the gathered result
-    hcl.all_gather_sim(shard, full, chunk_bytes=c["chunk_bytes"])
+            assert torch.equal(tot.to(torch.int32), shard[r]), r
+            del tot
+    other = [torch.zeros(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
+    assert hcl.reduce_scatter_sim(send, other, chunk_bytes=chunk, sched="fused") == 1
     torch.cuda.synchronize()
+    check_shards(other, "fused out of place")
     for r in range(W):
-        for q in range(W):
-            assert torch.equal(full[r][q * n:(q + 1) * n].view(torch.int16 if es == 2 else torch.int32),
-                               shard[q].view(torch.int16 if es == 2 else torch.int32)), (r, q)
+        assert torch.equal(_view_int(other[r]), _view_int(shard[r])), ("fused vs stepwise", r)
+    # the inputs are still what the seeds give (out of place leaves send[] alone)
+    probe = torch.empty(m, dtype=wl.TORCH_DTYPE[dtype], device="cuda")
+    wl.fill_rank(probe, wl.rank_seed(cfg_id, 3), c["dist"])
+    assert torch.equal(_view_int(probe), _view_int(send[3][:m]))
+    del other, probe
+
+    # --- Reduce-Scatter in place: STEPWISE, then (inputs drawn again) FUSED ---
+    inpl = [send[r][r * n:(r + 1) * n] for r in range(W)]
+    for sched in ("stepwise", "fused"):
+        hcl.reduce_scatter_sim(send, inpl, chunk_bytes=chunk, sched=sched)
+        torch.cuda.synchronize()
+        check_shards(inpl, f"{sched} in place")
+        for r in range(W):
+            assert torch.equal(_view_int(inpl[r]), _view_int(shard[r])), (sched, "in place", r)
+        if sched == "stepwise":
+            _fill_all(send, cfg_id, c["dist"])
+
+    # --- All-Gather of the shards; the inputs' memory now serves as the gathered vectors ---
+    full = send
+
+    def check_full(what):
+        for r in range(W):
+            for q in range(W):
+                assert torch.equal(_view_int(full[r][q * n:(q + 1) * n]), _view_int(shard[q])), (what, r, q)
+        # and against the oracle's windows, through the last elements of the 16 GiB buffers
+        for off in (0, n - m):
+            for q in range(W):
+                assert np.array_equal(wl.to_wire(full[W - 1 - q][q * n + off:q * n + off + m]), want[off][q]), (what, off, q)
+
+    for sched in ("stepwise", "fused"):
+        for t in full:
+            _view_int(t).fill_(0x55)
+        assert hcl.all_gather_sim(shard, full, chunk_bytes=chunk, sched=sched) == (W if sched == "stepwise" else 1)
+        torch.cuda.synchronize()
+        check_full(f"all-gather {sched}")
+    for t in full:
+        _view_int(t).fill_(0x33)
+    own = [full[r][r * n:(r + 1) * n] for r in range(W)]
+    for r in range(W):
+        own[r].copy_(shard[r])
+    assert hcl.all_gather_sim(own, full, chunk_bytes=chunk) == W - 1
+    torch.cuda.synchronize()
+    check_full("all-gather stepwise in place")
+
+
+def test_config5_named_size_host_staged_every_element():
+    """The host-staged All-Reduce at its named size: W = 8, 512 MiB of fp32 per rank, blocks
+    of 64 MiB travelling through pinned host memory; every element against the oracle."""
+    c = wl.CONFIGS[5]
+    W, count, dtype, chunk = c["W"], c["count"], c["dtype"], c["chunk_bytes"]
+    code = wl.DTYPE_CODE[dtype]
+    send = _device_inputs(5, W, count, dtype, c["dist"])
+    recv = [torch.zeros_like(t) for t in send]
+    nb = hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, W, count, code, chunk, xport="host_staged")
+    assert nb == 2 * W * (64 << 20)
+    stage = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
+    assert hcl.allreduce_sim(send, recv, chunk_bytes=chunk, xport="host_staged", host_stage=stage) == 2 * (W - 1) + 1
+    torch.cuda.synchronize()
+    work = [wl.to_wire(t) for t in send]
+    orc.set_threads(0)
+    orc.allreduce_inplace(work, code, chunk_elems=chunk // 4)
+    for r in range(W):
+        got = wl.to_wire(recv[r])
+        assert np.array_equal(got.view(np.uint32), work[r].view(np.uint32)), f"rank {r}: {(got != work[r]).sum()} elements differ"
+    for r in range(W):
+        probe = torch.empty(1 << 16, dtype=torch.float32, device="cuda")
+        wl.fill_rank(probe, wl.rank_seed(5, r), c["dist"])
+        assert torch.equal(probe, send[r][:1 << 16]), "send[] must stay untouched"

@@ -9,7 +9,8 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import (CODE, assert_same_bits, device_inputs, fresh, run_all_gather, run_alltoall, run_broadcast)
+from gpu_util import (CODE, assert_same_bits, check_guards, device_inputs, fresh, pinned_stage, run_all_gather,
+                      run_alltoall, run_broadcast)
 from oracle import ring_oracle as orc
 from paper_2601_22585_amd import hcl
 
@@ -35,6 +36,8 @@ def _case(rnd):
     c["order"] = rnd.choice(["ring", "tree"]) if sched == "fused" else "ring"
     c["acc"] = rnd.choice(["per_hop", "fp32"]) if sched == "fused" else "per_hop"
     c["fuse"] = sched == "stepwise" and c["kind"] == "allreduce" and rnd.random() < 0.3
+    # blocks travelling through pinned host memory: STEPWISE All-Reduce and Reduce-Scatter have that transport
+    c["xport"] = "host_staged" if (sched == "stepwise" and c["kind"] != "reduce" and rnd.random() < 0.3) else "direct"
     n = rnd.choice([1, 17, 1000, 4096, 65_536, rnd.randrange(1, 200_000)])
     c["n"] = n
     chunk_elems = rnd.choice([0, 0, 1, 16, 1024, 8192, rnd.randrange(1, 50_000)])
@@ -51,8 +54,11 @@ def _run(c, seed):
                rounding=orc.ROUND_ONCE if c["acc"] == "fp32" else orc.ROUND_EACH)
     opt = dict(chunk_bytes=c["chunk"], ring=c["ring"], sched=c["sched"], op=c["op"], order=c["order"],
                accumulate=c["acc"], threads=c["threads"], unroll=c["unroll"], blocks=c["blocks"],
-               nontemporal=c["nontemporal"])
+               nontemporal=c["nontemporal"], xport=c["xport"])
     tag = f"seed {seed}: {c}"
+    if c["xport"] == "host_staged":
+        kind = hcl.KIND_ALLREDUCE if c["kind"] == "allreduce" else hcl.KIND_REDUCE_SCATTER
+        opt["host_stage"] = pinned_stage(hcl.host_stage_bytes(kind, W, n, code, c["chunk"], xport="host_staged"))
     if c["kind"] == "allreduce":
         cpu, dev = device_inputs(seed, W, n, dtype, DIST[dtype], c["mis"])
         wire = [wl.to_wire(t) for t in cpu]
@@ -72,7 +78,7 @@ def _run(c, seed):
             recv = [dev[r][r * n:(r + 1) * n] for r in range(W)]
         else:
             recv = fresh(W, n, dtype, c["mis"], fill=0)
-            wsb = hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, code, c["chunk"], sched=c["sched"])
+            wsb = hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, code, c["chunk"], sched=c["sched"], xport=c["xport"])
             if wsb:
                 opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
         hcl.reduce_scatter_sim(dev, recv, **opt)
@@ -93,6 +99,7 @@ def _run(c, seed):
         hcl.reduce_sim(dev, out, root, **opt)
         torch.cuda.synchronize()
         assert_same_bits(out[root], want, dtype, tag)
+    check_guards()
 
 
 @pytest.mark.parametrize("batch", range(3))
@@ -110,6 +117,8 @@ def test_random_configurations_of_the_copying_collectives(batch):
                    threads=rnd.choice([0, 0, 64, 256]), unroll=rnd.choice([0, 0, 1, 2, 4]),
                    blocks=rnd.choice([0, 0, 5, 300]))
         kind = rnd.choice(["all_gather", "broadcast", "alltoall"])
+        if kind == "all_gather" and opt["sched"] == "stepwise" and rnd.random() < 0.4:
+            opt["xport"] = "host_staged"
         if kind == "all_gather":
             run_all_gather(seed, W, n, dtype, DIST[dtype], inplace=rnd.random() < 0.3 and opt["misalign"] == 0, **opt)
         elif kind == "broadcast":
