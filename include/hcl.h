@@ -63,7 +63,9 @@ extern "C" {
 #endif
 
 #define HCL_MAX_RANKS 16
-#define HCL_VERSION 102
+#define HCL_VERSION 103
+/* size of the library-owned scratch array behind hcl_reduce_scatter_sim_static */
+#define HCL_STATIC_SCRATCH_BYTES (32u << 20)
 
 typedef enum {
   HCL_OK = 0,
@@ -208,6 +210,28 @@ hcl_status_t hcl_allreduce_sim(const void *const *send, void *const *recv, int W
 hcl_status_t hcl_reduce_scatter_sim(const void *const *send, void *const *recv, int W, size_t recvcount,
                                     hcl_dtype_t dtype, hcl_op_t op, size_t chunk_bytes,
                                     const hcl_opts_t *opts, void *stream);
+
+/*
+ * Reduce-Scatter for callers that cannot allocate device memory or bring a
+ * workspace along: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, semantics and result bits
+ * as hcl_reduce_scatter_sim, except that opts->workspace is ignored: where that
+ * entry point needs a workspace (out of place, STEPWISE, DIRECT, W > 2) the
+ * partial sums live in an array of HCL_STATIC_SCRATCH_BYTES (32 MiB) that is
+ * part of the library's code object -- every GPU the process uses holds one copy
+ * until the process ends.  The call allocates and frees nothing.  A call whose
+ * partial sums need more than that (hcl_workspace_bytes(HCL_KIND_REDUCE_SCATTER,
+ * ...) > HCL_STATIC_SCRATCH_BYTES, i.e. blocks beyond 32 MiB / (2 W)) returns
+ * HCL_ERR_WORKSPACE and launches nothing.  Nothing in the array has to be
+ * cleared between calls (each partial is written before it is read), but all
+ * calls on one GPU share it: two such calls may not overlap in time on the same
+ * GPU (different streams, or graphs replayed concurrently) -- they would race.
+ */
+hcl_status_t hcl_reduce_scatter_sim_static(const void *const *send, void *const *recv, int W,
+                                           size_t recvcount, hcl_dtype_t dtype, hcl_op_t op,
+                                           size_t chunk_bytes, const hcl_opts_t *opts, void *stream);
+/* HCL_STATIC_SCRATCH_BYTES as the built library has it. */
+size_t hcl_static_scratch_bytes(void);
 
 /*
  * All-Gather: the parameter half of ZeRO-3 (same passages).  send[r] holds

@@ -7,8 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhcl.so")
-SOURCES = ["hcl_api.cpp", "reduce_copy.hip", "ring_fused.hip"]   # ring_fused.hip is compiled once per wire type and part
-HEADERS = ["reduce_copy.h", "ring_sched.h", "wire.h"]
+SOURCES = ["hcl_api.cpp", "reduce_copy.hip", "ring_fused.hip", "static_scratch.hip"]   # ring_fused.hip is compiled once per wire type and part
+HEADERS = ["reduce_copy.h", "ring_sched.h", "wire.h", "internal.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -36,7 +36,8 @@ def build_lib(force=True, verbose=False):
     os.makedirs(objdir, exist_ok=True)
     # translation units: the API, the step kernels, and the fused kernels once per
     # (wire type, part) -- compiled side by side, then one link
-    units = [("hcl_api.cpp", "hcl_api", []), ("reduce_copy.hip", "reduce_copy", [])]
+    units = [("hcl_api.cpp", "hcl_api", []), ("reduce_copy.hip", "reduce_copy", []),
+             ("static_scratch.hip", "static_scratch", [])]
     for dt in range(7):
         for part in range(2):
             units.append(("ring_fused.hip", f"ring_fused_dt{dt}_p{part}", [f"-DHCL_FUSED_DT={dt}", f"-DHCL_FUSED_PART={part}"]))

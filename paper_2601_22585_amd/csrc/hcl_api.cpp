@@ -9,6 +9,7 @@
 #include <cstring>
 
 #include "hcl.h"
+#include "internal.h"
 #include "reduce_copy.h"
 #include "ring_sched.h"
 
@@ -19,7 +20,7 @@ using namespace hcl;
 // ---------------------------------------------------------------------------
 static thread_local char g_err[512] = "";
 
-static hcl_status_t fail(hcl_status_t st, const char* fmt, ...) {
+hcl_status_t hcl::fail(hcl_status_t st, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof g_err, fmt, ap);

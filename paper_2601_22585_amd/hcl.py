@@ -38,6 +38,7 @@ EXPORTS = [
     "hcl_host_stage_bytes", "hcl_ring_step", "hcl_schedule_items", "hcl_events_create",
     "hcl_events_destroy", "hcl_event_record", "hcl_event_elapsed_ms", "hcl_device_cu_count",
     "hcl_status_string", "hcl_last_error", "hcl_version",
+    "hcl_reduce_scatter_sim_static", "hcl_static_scratch_bytes",
 ]
 
 
@@ -96,6 +97,8 @@ def lib():
     L.hcl_allreduce_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
                                     ctypes.c_size_t, op, ctypes.c_void_p]
     L.hcl_reduce_scatter_sim.argtypes = L.hcl_allreduce_sim.argtypes
+    L.hcl_reduce_scatter_sim_static.argtypes = L.hcl_allreduce_sim.argtypes
+    L.hcl_static_scratch_bytes.restype = ctypes.c_size_t
     L.hcl_all_gather_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
                                      ctypes.c_size_t, op, ctypes.c_void_p]
     L.hcl_reduce_sim.argtypes = [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -241,6 +244,20 @@ def reduce_scatter_sim(send, recv, chunk_bytes=0, dtype=None, op=SUM, stream=Non
     _check(lib().hcl_reduce_scatter_sim(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), _op_code(op),
                                         chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
     return o.n_launches.contents.value
+
+
+def reduce_scatter_sim_static(send, recv, chunk_bytes=0, dtype=None, op=SUM, stream=None, recvcount=None, **opt):
+    """Reduce-Scatter whose partial sums live in the library's own fixed scratch array (no workspace)."""
+    W = len(send)
+    o, keep = make_opts(W, **opt)
+    n = recv[0].numel() if recvcount is None else recvcount
+    _check(lib().hcl_reduce_scatter_sim_static(_ptrs(send), _ptrs(recv), W, n, _dtype_code(send, dtype), _op_code(op),
+                                               chunk_bytes, ctypes.byref(o), _stream_handle(stream)))
+    return o.n_launches.contents.value
+
+
+def static_scratch_bytes():
+    return lib().hcl_static_scratch_bytes()
 
 
 def all_gather_sim(send, recv, chunk_bytes=0, dtype=None, stream=None, sendcount=None, **opt):
