@@ -98,8 +98,15 @@ def parse():
     ap.add_argument("--chunk-bytes", type=int, default=-1)
     ap.add_argument("--graph", action="store_true",
                     help="capture one call into a HIP graph and time K replays (latency regime; no events)")
-    ap.add_argument("--skew-bytes", type=int, default=0,
-                    help="start the k-th allocated buffer k * skew bytes into its allocation (layout experiments)")
+    ap.add_argument("--pad-bytes", type=int, default=0,
+                    help="gap between consecutive rank buffers inside the one allocation they are carved from "
+                         "(a multiple of 256; layout experiments)")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="give every rank buffer an allocation of its own instead of carving all of them out of one")
+    ap.add_argument("--chains", type=int, default=1, choices=[1, 2],
+                    help="2: stepwise schedule with the chunk range split over two streams (opts.aux_stream)")
+    ap.add_argument("--no-cache-free-probe", action="store_true",
+                    help="default workload only: skip the extra measurement of the dominant kernel at a footprint far beyond the last-level cache")
     return ap.parse_args()
 
 
@@ -153,12 +160,36 @@ def main():
         name = f"{name}:{op}"
 
     # ---- buffers: seeded inputs generated on the device ----
-    nalloc = [0]
+    # All rank buffers (and the workspace) are carved out of ONE allocation at fixed relative
+    # offsets, in the order they are asked for, each starting on a 256-byte boundary: where the
+    # buffers lie relative to each other is then the same in every process.
+    assert args.pad_bytes % 256 == 0
+    plan = []          # (elements, dtype) in request order; filled in by new(), resolved by carve()
 
-    def new(n):
-        pad = (nalloc[0] * args.skew_bytes) // es
-        nalloc[0] += 1
-        return torch.empty(n + pad, dtype=wl.TORCH_DTYPE[dtype], device="cuda")[pad:]
+    class Slot:
+        def __init__(self, n, td):
+            self.n, self.td, self.t = n, td, None
+
+    def new(n, td=None):
+        sl = Slot(n, td or wl.TORCH_DTYPE[dtype])
+        plan.append(sl)
+        return sl
+
+    def carve():
+        if args.separate_allocations:
+            for sl in plan:
+                sl.t = torch.empty(sl.n, dtype=sl.td, device="cuda")
+            return None
+        offs, total = [], 0
+        for sl in plan:
+            offs.append(total)
+            nb = sl.n * torch.empty(0, dtype=sl.td).element_size()
+            total += -(-nb // 256) * 256 + args.pad_bytes
+        arena = torch.empty(total, dtype=torch.uint8, device="cuda")
+        for sl, o in zip(plan, offs):
+            nb = sl.n * torch.empty(0, dtype=sl.td).element_size()
+            sl.t = arena[o:o + nb].view(sl.td)
+        return arena
 
     opt = dict(sched=args.sched, xport=xport, threads=args.threads, blocks=args.blocks, unroll=args.unroll,
                nontemporal=args.nontemporal)
@@ -170,50 +201,65 @@ def main():
     if args.reduce_op != "sum":
         assert reducing, "--reduce-op applies to allreduce, reduce_scatter and reduce"
         opt["op"] = args.reduce_op
+    ws_slot = None
     if op == "allreduce":
         opt["fuse_rs_ag"] = args.fuse_rs_ag
-        send = [new(count) for _ in range(W)]
-        recv = send if args.inplace else [new(count) for _ in range(W)]
+        send_s = [new(count) for _ in range(W)]
+        recv_s = send_s if args.inplace else [new(count) for _ in range(W)]
         kind = hcl.KIND_ALLREDUCE
         call = hcl.allreduce_sim
         per_call_count = count
     elif op == "reduce_scatter":
-        send = [new(count) for _ in range(W)]
-        recv = [send[r][r * B:(r + 1) * B] for r in range(W)] if args.inplace else [new(B) for _ in range(W)]
+        send_s = [new(count) for _ in range(W)]
+        recv_s = None if args.inplace else [new(B) for _ in range(W)]
         kind = hcl.KIND_REDUCE_SCATTER
         call = hcl.reduce_scatter_sim
         per_call_count = B
         if not args.inplace:
             wsb = hcl.workspace_bytes(kind, W, B, code, chunk_bytes, sched=args.sched, xport=xport)
             if wsb:
-                opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+                ws_slot = new(wsb, torch.uint8)
     elif op == "all_gather":
-        recv = [new(count) for _ in range(W)]
-        send = [recv[r][r * B:(r + 1) * B] for r in range(W)] if args.inplace else [new(B) for _ in range(W)]
+        recv_s = [new(count) for _ in range(W)]
+        send_s = None if args.inplace else [new(B) for _ in range(W)]
         kind = hcl.KIND_ALL_GATHER
         call = hcl.all_gather_sim
         per_call_count = B
     elif op == "reduce":
-        send = [new(count) for _ in range(W)]
-        recv = [send[0] if args.inplace else new(count)] + [None] * (W - 1)
+        send_s = [new(count) for _ in range(W)]
+        recv_s = [send_s[0] if args.inplace else new(count)] + [None] * (W - 1)
         kind = hcl.KIND_REDUCE
         call = lambda s_, r_, **kw: hcl.reduce_sim(s_, r_, 0, **kw)
         per_call_count = count
         wsb = hcl.workspace_bytes(kind, W, count, code, chunk_bytes, sched=args.sched)
         if wsb:
-            opt["workspace"] = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+            ws_slot = new(wsb, torch.uint8)
     elif op == "broadcast":
-        recv = [new(count) for _ in range(W)]
-        send = [recv[0] if args.inplace else new(count)] + [None] * (W - 1)
+        recv_s = [new(count) for _ in range(W)]
+        send_s = [recv_s[0] if args.inplace else new(count)] + [None] * (W - 1)
         kind = hcl.KIND_BROADCAST
         call = lambda s_, r_, **kw: hcl.broadcast_sim(s_, r_, 0, **kw)
         per_call_count = count
     else:
-        send = [new(count) for _ in range(W)]
-        recv = [new(count) for _ in range(W)]
+        send_s = [new(count) for _ in range(W)]
+        recv_s = [new(count) for _ in range(W)]
         kind = hcl.KIND_ALLTOALL
         call = hcl.alltoall_sim
         per_call_count = B
+    arena = carve()
+    tens = lambda slots: None if slots is None else [None if x is None else x.t for x in slots]
+    send, recv = tens(send_s), tens(recv_s)
+    if op == "reduce_scatter" and args.inplace:
+        recv = [send[r][r * B:(r + 1) * B] for r in range(W)]
+    if op == "all_gather" and args.inplace:
+        send = [recv[r][r * B:(r + 1) * B] for r in range(W)]
+    if ws_slot is not None:
+        opt["workspace"] = ws_slot.t
+    aux = None
+    if args.chains == 2:
+        assert args.sched == "stepwise", "--chains 2 applies to the stepwise schedule"
+        aux = (torch.cuda.Stream(), hcl.EventList(2))
+        opt["aux_stream"], opt["aux_events"] = aux
 
     def refill():
         for r in range(W):
@@ -243,39 +289,29 @@ def main():
             ins = [np.concatenate([wl.to_wire(send[r][lo:hi]) for lo, hi in win]) for r in range(W)]
         wide = args.accumulate == "fp32"
         oop = {"sum": orc.SUM, "prod": orc.PROD, "max": orc.MAX, "min": orc.MIN}[args.reduce_op]
-        variant = wide or args.order == "tree"      # the closed-form replay; otherwise the ring as message passing
-        vkw = dict(op=oop, order=orc.ORDER_TREE if args.order == "tree" else orc.ORDER_RING,
-                   rounding=orc.ROUND_ONCE if wide else orc.ROUND_EACH)
-        fn = {"allreduce": (lambda a, c_, chunk_elems=0: orc.allreduce_var(a, c_, **vkw)) if variant
-                           else (lambda a, c_, chunk_elems=0: orc.allreduce(a, c_, chunk_elems=chunk_elems, op=oop)),
-              "reduce_scatter": (lambda a, c_, chunk_elems=0: orc.reduce_scatter_var(a, c_, **vkw)) if variant
-                                else (lambda a, c_, chunk_elems=0: orc.reduce_scatter(a, c_, chunk_elems=chunk_elems, op=oop)),
-              "all_gather": orc.all_gather,
-              "reduce": lambda a, c_, chunk_elems=0: [orc.reduce_var(a, c_, 0, **vkw) if variant
-                                                      else orc.reduce(a, c_, 0, chunk_elems=chunk_elems, op=oop)],
-              "broadcast": lambda a, c_, chunk_elems=0: orc.broadcast(a[0], c_, W, 0),
-              "alltoall": lambda a, c_, chunk_elems=0: orc.alltoall(a, c_)}[op]
-        # one thread first, on an eighth of the sample, then every host core on all of it
+        # the closed-form replay for the reordered modes; otherwise the ring as message passing
+        rkw = dict(op=oop, order=orc.ORDER_TREE if args.order == "tree" else orc.ORDER_RING,
+                   rounding=orc.ROUND_ONCE if wide else orc.ROUND_EACH, W=W, root=0)
+        if op in ("all_gather", "broadcast", "alltoall"):
+            rkw.update(op=orc.SUM, order=orc.ORDER_RING, rounding=orc.ROUND_EACH)
+        # one thread first, on an eighth of the sample, then every host core on all of it; the
+        # clock runs around the replay only (working copies are made before it starts)
         m1 = max(1, m // 8)
         if op == "all_gather":
             small = [a[:m1] for a in ins]
         else:
             small = [np.concatenate([a[c * m:c * m + m1] for c in range(W)]) for a in ins]
         orc.set_threads(1)
-        t0 = time.perf_counter()
-        fn(small, code, chunk_elems=min(ce, m1))
-        t_one = time.perf_counter() - t0
+        _, t_one = orc.replay_timed(op, small, code, chunk_elems=min(ce, m1), **rkw)
         del small
         threads = orc.set_threads(os.cpu_count() or 1)
-        t0 = time.perf_counter()
-        want = fn(ins, code, chunk_elems=ce)
-        t_cpu = time.perf_counter() - t0
+        want, t_cpu = orc.replay_timed(op, ins, code, chunk_elems=ce, **rkw)
         del ins
         sample_bytes = W * m * es      # bytes of the sampled full vector, per rank
         cpu_baseline = {"value": round(sample_bytes / t_cpu / 1e9, 6), "unit": "GB/s", "cores": threads, "kind": "oracle",
                         "sample": f"{op}: leading {m} of {B} elements of each of the {W} blocks of every rank "
                                   f"({sample_bytes / 2**20:.1f} MiB of vector per rank), replayed in {t_cpu:.2f} s "
-                                  f"(input copies included)",
+                                  f"(wall clock around the replay only)",
                         "seconds": round(t_cpu, 3),
                         "one_thread": {"value": round(W * m1 * es / t_one / 1e9, 6), "unit": "GB/s",
                                        "sample_MiB_per_rank": round(W * m1 * es / 2**20, 2), "seconds": round(t_one, 3)}}
@@ -427,6 +463,35 @@ def main():
                                 "what": "plain copy of the same buffers by reduce_copy_vec<copy,1,1> (W launches, gaps included)",
                                 "frac_of_it": round(roof["achieved"] / copy_gbps, 4)}
 
+    # ---- the same step kernel where no cache can help: the in-place Reduce-Scatter of the ZeRO-style
+    # workload (W = 8, 2 GiB blocks, 16 GiB per rank: every launch moves 48 GiB, the last-level cache
+    # holds 256 MiB).  At the headline size the partial sums one step writes (256 MiB in all) are what
+    # the next step reads, so part of its reads may be served from that cache, which the HBM counters
+    # cannot tell apart.  Default workload only; outside the timed region.
+    if (roof is not None and args.config == 2 and op == "allreduce" and args.sched == "stepwise" and not args.bytes_per_rank
+            and not args.no_cache_free_probe and torch.cuda.mem_get_info()[0] > (140 << 30)):
+        c4 = wl.CONFIGS[4]
+        n4 = c4["count"] // c4["W"]
+        big = [torch.empty(n4 * c4["W"], dtype=torch.bfloat16, device="cuda") for _ in range(c4["W"])]
+        for r in range(c4["W"]):
+            wl.fill_rank(big[r], wl.rank_seed(4, r), c4["dist"])
+        shards = [big[r][r * n4:(r + 1) * n4] for r in range(c4["W"])]
+        reps = 3
+        pev = hcl.EventList(2 * (reps + 1))
+        for k in range(reps + 1):
+            hcl.reduce_scatter_sim(big, shards, chunk_bytes=c4["chunk_bytes"], stream=stream,
+                                   events=(pev, 2 * k, 2), events_per_phase=True)
+        torch.cuda.synchronize()
+        ms4 = sum(pev.elapsed_ms(2 * k, 2 * k + 1) for k in range(1, reps + 1)) / reps / (c4["W"] - 1)
+        pev.close()
+        b4 = 3 * n4 * c4["W"] * 2
+        roof["cache_free"] = {"workload": "cfg4_rs_ag_w8_bf16_2GiB_shard:reduce_scatter, in place",
+                              "kernel": "reduce_copy_vec<bf16,NSRC=2,NDST=1> (one wavefront x 1 vector per workgroup at this size)",
+                              "bytes_per_launch": b4, "avg_launch_ms": round(ms4, 4),
+                              "achieved": round(b4 / (ms4 * 1e-3) / 1e9, 1), "unit": "GB/s",
+                              "frac": round(b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del big, shards
+
     value = S / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "ring all-reduce algorithm GB/s on 1 MI355X" if op == "allreduce"
@@ -437,7 +502,9 @@ def main():
         "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
                    "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
                    "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph), "accumulate": args.accumulate,
-                   "reduce_op": args.reduce_op if reducing else None, "order": args.order},
+                   "reduce_op": args.reduce_op if reducing else None, "order": args.order, "chains": args.chains,
+                   "layout": "separate allocations" if args.separate_allocations
+                             else f"all buffers carved from one allocation, 256-byte aligned, {args.pad_bytes} bytes between them"},
         "algbw_rank_equiv_GBps": round(W * value, 2),
         "call_hbm_GBps": round(call_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "call_hbm_frac_of_peak": round(call_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

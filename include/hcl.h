@@ -36,8 +36,9 @@
  *   - W in [1, 16].  count == 0 is HCL_OK and a no-op.  chunk_bytes == 0 means
  *     one chunk per block; otherwise it must be a positive multiple of the
  *     element size.  A chunk only orders the work inside a block.
- *   - Base pointers must be aligned to the element size; nothing more is
- *     required.  Every path moves 128-bit vectors at whatever address the data
+ *   - Rank buffers must be aligned to the element size; nothing more is
+ *     required of them (opts->workspace and opts->host_stage must be 16-byte
+ *     aligned).  Every path moves 128-bit vectors at whatever address the data
  *     has; buffers that are not 16-byte aligned (or not congruent modulo 128
  *     bytes with each other) make accesses straddle cache lines and measured
  *     10-25 % slower on MI355X than 256-byte aligned ones.
@@ -47,8 +48,11 @@
  *     collide in DRAM; offsetting the buffers against each other by odd amounts
  *     (64 KiB + 256 B, say) measured 3-7 % slower on MI355X.
  *   - Launch-shape fields of hcl_opts_t that are 0 may be overridden by the
- *     environment variables HCL_THREADS, HCL_UNROLL, HCL_BLOCKS and
- *     HCL_NONTEMPORAL (for sweeps); values in the struct win.
+ *     environment variables HCL_THREADS, HCL_UNROLL, HCL_BLOCKS,
+ *     HCL_NONTEMPORAL and HCL_STAGGER (for sweeps); values in the struct win.
+ *   - HCL_DEBUG=1 in the environment makes every collective call print its
+ *     arguments and the work items of its schedule (hcl_schedule_items) to
+ *     stderr before it enqueues anything.
  *   - Calls are re-entrant; the only global state is cached device properties
  *     and the thread-local error string.
  */
@@ -167,6 +171,15 @@ typedef struct hcl_opts {
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
   int accumulate;          /* hcl_acc_t; anything but PER_HOP needs sched == FUSED           */
   int order;               /* hcl_order_t; TREE needs sched == FUSED                          */
+  void *aux_stream;        /* STEPWISE only, optional: a second hipStream_t.  The chunks of every step
+                              are split in two halves; the second half's launches go to this stream,
+                              as a dependency chain of their own (chunk j of a step needs only chunk
+                              j of the step before), forked from `stream` before its first launch and
+                              joined back before the call returns -- one chain's kernel runs while the
+                              other chain is between two kernels.  Same bits.  Both streams must have
+                              the same (default) priority; legal under stream capture of `stream`    */
+  void *const *aux_events; /* with aux_stream: host array of two hipEvent_t (hcl_events_create makes
+                              them) used for the fork and the join; the library creates no events    */
 } hcl_opts_t;
 
 /* One unit of the ring schedule, as hcl_schedule_items reports it. */
@@ -184,9 +197,9 @@ typedef struct hcl_work_item {
 } hcl_work_item_t;
 
 /*
- * All-Reduce (sum).  send[r] and recv[r] hold `count` elements; afterwards
- * every recv[r] holds the ring-order sum over all ranks (bit-identical across
- * ranks).  The vector is cut into W blocks of ceil(count / W) elements; the
+ * All-Reduce.  send[r] and recv[r] hold `count` elements; afterwards every
+ * recv[r] holds the ring-order reduction (operator `op`) over all ranks
+ * (bit-identical across ranks).  The vector is cut into W blocks of ceil(count / W) elements; the
  * collective is W-1 Reduce-Scatter steps then W-1 All-Gather steps (Section 1;
  * Appendix B.1 "Communication patterns in DL"; Appendix D.4).
  * In place: recv[r] == send[r] for every r (all ranks or none).  Otherwise
@@ -198,10 +211,10 @@ hcl_status_t hcl_allreduce_sim(const void *const *send, void *const *recv, int W
                                const hcl_opts_t *opts, void *stream);
 
 /*
- * Reduce-Scatter (sum): the gradient half of ZeRO-2/3 (Appendix D.4, Table
+ * Reduce-Scatter: the gradient half of ZeRO-2/3 (Appendix D.4, Table
  * "Communication patterns across DeepSpeed ZeRO stages").  send[r] holds
  * W * recvcount elements, recv[r] receives recvcount elements = block r of the
- * ring-order sum.
+ * ring-order reduction (operator `op`).
  * In place: recv[r] == send[r] + r * recvcount (elements) for every r; the
  * other blocks of send[r] are then used for partial sums and left undefined.
  * Out of place with the STEPWISE schedule and W > 2, partial sums live in
@@ -243,12 +256,12 @@ hcl_status_t hcl_all_gather_sim(const void *const *send, void *const *recv, int 
                                 const hcl_opts_t *opts, void *stream);
 
 /*
- * Reduce (sum) to `root` along the ring -- one of the further collectives the
+ * Reduce to `root` along the ring -- one of the further collectives the
  * paper evaluates (Appendix E.1 "Other Collective Communication Operations").
  * send[r] holds `count` elements for every rank; only recv[root] is written
  * (the other recv entries are ignored and may be NULL).  The rank after the
- * root sends its vector on, every following rank adds its own with one hop, the
- * chain ends at the root: the sum runs in the order next(root), ..., root, i.e.
+ * root sends its vector on, every following rank combines its own with one hop, the
+ * chain ends at the root: the reduction runs in the order next(root), ..., root, i.e.
  * as block `root` of the All-Reduce does.  In place: recv[root] == send[root].
  * STEPWISE (W - 1 launches) with W > 2 keeps the travelling partial in
  * opts->workspace (hcl_workspace_bytes with HCL_KIND_REDUCE: two slots of the
@@ -281,30 +294,43 @@ hcl_status_t hcl_alltoall_sim(const void *const *send, void *const *recv, int W,
                               hcl_dtype_t dtype, size_t chunk_bytes,
                               const hcl_opts_t *opts, void *stream);
 
-/* Device scratch the call of this kind and shape needs in opts->workspace
- * (0 for everything except a STEPWISE Reduce with W > 2 -- two slots of the
- * vector -- and an out-of-place STEPWISE Reduce-Scatter with W > 2,
- * where the caller cannot say "in place" here: the figure is the out-of-place
- * one: 2 * W slots of one block rounded up to 256 bytes).  `count` is the per-call count argument of that entry point.  Returns
- * 0 on invalid arguments too. */
+/* Device scratch a call of this kind and shape needs in opts->workspace: where the
+ * travelling partial sums live when they can live in neither send[] nor recv[]
+ * (the library's counterpart of the vendor library's internal buffers, Section
+ * 4.2).  `count` is the count argument of that kind's entry point.
+ *   - STEPWISE, DIRECT Reduce-Scatter with W > 2: 2 * W slots; the figure is the
+ *     out-of-place one (the in-place form keeps its partial sums in send[] and
+ *     ignores the workspace; this query cannot know which form the call will be).
+ *   - STEPWISE Reduce with W > 2: 2 slots.
+ *   - everything else: 0.
+ * A slot is one block (Reduce: the vector) rounded up to 256 bytes, plus 4 KiB.
+ * opts->workspace must be 16-byte aligned.  Returns 0 on invalid arguments too. */
 size_t hcl_workspace_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                            const hcl_opts_t *opts);
 
-/* Pinned host memory the HOST_STAGED transport needs in opts->host_stage:
- * two inbox slots (one block rounded up to 256 bytes each) per rank.  0 for the DIRECT transport. */
+/* Pinned host memory the HOST_STAGED transport needs in opts->host_stage (the
+ * staging buffers of the host-staged path, Section 2.1 "Inter-node communication
+ * and RDMA"; Appendix F.1): two inbox slots per rank, each one block rounded up to
+ * 256 bytes, plus 4 KiB.  0 for the DIRECT transport.  opts->host_stage must be
+ * 16-byte aligned. */
 size_t hcl_host_stage_bytes(int kind, int W, size_t count, hcl_dtype_t dtype, size_t chunk_bytes,
                             const hcl_opts_t *opts);
 
-/* Ring chunk scheduler, host only.  Which block `rank` sends and which it
- * receives at (phase, step): Reduce-Scatter step s sends
+/* Ring chunk scheduler, host only: the message partitioning that the paper's
+ * library leaves to the vendor library's host side (Section 4.2), written out
+ * for the textbook ring.  Which block `rank` sends and which it receives at
+ * (phase, step): Reduce-Scatter step s sends
  * ring[(pos - s - 1) mod W] and receives (and reduces) ring[(pos - s - 2) mod W];
  * All-Gather step s sends ring[(pos - s) mod W] and receives
  * ring[(pos - s - 1) mod W], pos being the rank's index in ring[]. */
 hcl_status_t hcl_ring_step(int W, const int *ring, int phase, int step, int rank,
                            int *send_block, int *recv_block);
 
-/* Enumerates the work items of one ring step (every rank, every chunk, in
- * launch order: chunk-major, then ring position) for a vector of W blocks of
+/* The same partitioning (Section 4.2) down to chunks: enumerates the work items
+ * of one ring step (every rank, every chunk, chunk-major, then ring position).
+ * This is a description of the schedule for inspection, tests and the HCL_DEBUG
+ * dump; no kernel consumes the list -- a launch carries one segment per rank and
+ * its workgroups derive (chunk, rank, offset) from their tile index.  For a vector of W blocks of
  * `block_elems` elements where the last block may be shorter: `count` is the
  * full vector length (All-Reduce: count; RS / AG: W * per-rank count).
  * Writes at most max_items items and always reports the total in *n_items.

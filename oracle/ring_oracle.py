@@ -303,3 +303,93 @@ def f16_to_f32(x):
     y = np.empty(x.shape, np.float32)
     lib().orc_f16_to_f32_n(x.ctypes.data, y.ctypes.data, x.size)
     return y
+
+
+def replay_timed(kind, inputs, dtype, ring=None, chunk_elems=0, op=SUM, root=0, order=ORDER_RING,
+                 rounding=ROUND_EACH, W=None):
+    """One collective with the wall clock around the C replay only: working copies and
+    output arrays are made, and their pages touched, before the clock starts.
+    kind: "allreduce" | "reduce_scatter" | "all_gather" | "reduce" | "broadcast" | "alltoall";
+    (order, rounding) other than (RING, EACH) selects the closed-form variant replay.
+    Returns (result as the untimed functions give it, seconds)."""
+    import time
+    L = lib()
+    variant = order != ORDER_RING or rounding != ROUND_EACH
+    ra = _ring_arg(ring, len(inputs) if kind != "broadcast" else W)
+    if kind == "broadcast":
+        src = _wire(inputs[0], dtype)
+        out = [np.zeros(src.size, dtype=NP_WIRE[dtype]) for _ in range(W)]
+        po = _ptrs(out)
+        t0 = time.perf_counter()
+        rc = L.orc_broadcast(src.ctypes.data, po, W, src.size, dtype, ra, root)
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return out, dt
+    W = len(inputs)
+    src = [_wire(a, dtype) for a in inputs]
+    n = src[0].size
+    if kind == "allreduce" and not variant:
+        work = [a.copy() for a in src]
+        pw = _ptrs(work)
+        t0 = time.perf_counter()
+        rc = (L.orc_allreduce(pw, W, n, dtype, ra, chunk_elems) if op == SUM
+              else L.orc_allreduce_op(pw, W, n, dtype, op, ra, chunk_elems))
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return work, dt
+    if kind == "allreduce":
+        out = [np.zeros(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+        ps, po = _ptrs(src), _ptrs(out)
+        t0 = time.perf_counter()
+        rc = L.orc_allreduce_var(ps, po, W, n, dtype, op, ra, order, rounding)
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return out, dt
+    if kind == "reduce_scatter":
+        assert n % W == 0
+        out = [np.zeros(n // W, dtype=NP_WIRE[dtype]) for _ in range(W)]
+        po = _ptrs(out)
+        if variant:
+            ps = _ptrs(src)
+            t0 = time.perf_counter()
+            rc = L.orc_reduce_scatter_var(ps, po, W, n // W, dtype, op, ra, order, rounding)
+        else:
+            work = [a.copy() for a in src]
+            pw = _ptrs(work)
+            t0 = time.perf_counter()
+            rc = (L.orc_reduce_scatter(pw, po, W, n // W, dtype, ra, chunk_elems) if op == SUM
+                  else L.orc_reduce_scatter_op(pw, po, W, n // W, dtype, op, ra, chunk_elems))
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return out, dt
+    if kind == "all_gather":
+        out = [np.zeros(W * n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+        ps, po = _ptrs(src), _ptrs(out)
+        t0 = time.perf_counter()
+        rc = L.orc_all_gather(ps, po, W, n, dtype, ra, chunk_elems)
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return out, dt
+    if kind == "reduce":
+        out = np.zeros(n, dtype=NP_WIRE[dtype])
+        ps = _ptrs(src)
+        t0 = time.perf_counter()
+        if variant:
+            rc = L.orc_reduce_var(ps, out.ctypes.data, W, n, dtype, op, ra, root, order, rounding)
+        elif op == SUM:
+            rc = L.orc_reduce(ps, out.ctypes.data, W, n, dtype, ra, root, chunk_elems)
+        else:
+            rc = L.orc_reduce_op(ps, out.ctypes.data, W, n, dtype, op, ra, root, chunk_elems)
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return [out], dt
+    if kind == "alltoall":
+        assert n % W == 0
+        out = [np.zeros(n, dtype=NP_WIRE[dtype]) for _ in range(W)]
+        ps, po = _ptrs(src), _ptrs(out)
+        t0 = time.perf_counter()
+        rc = L.orc_alltoall(ps, po, W, n // W, dtype)
+        dt = time.perf_counter() - t0
+        _check(rc, kind)
+        return out, dt
+    raise ValueError(kind)

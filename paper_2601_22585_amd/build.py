@@ -67,21 +67,28 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
+EXAMPLES = ["allreduce_latency", "allreduce_from_file"]
+
+
 def build_examples(verbose=False):
-    """Compile the plain-C example against the built library (it links libhcl.so by path)."""
+    """Compile the plain-C examples against the built library (they link libhcl.so by path).
+    Returns the executables' paths."""
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    src = os.path.join(HERE, "examples", "allreduce_latency.c")
-    exe = os.path.join(HERE, "examples", "allreduce_latency")
-    cmd = ["gcc", "-O2", "-std=gnu11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
-           "-I", os.path.join(ROOT, "include"), src, LIB, "-L", os.path.join(rocm, "lib"), "-lamdhip64",
-           "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return exe
+    exes = []
+    for name in EXAMPLES:
+        src = os.path.join(HERE, "examples", name + ".c")
+        exe = os.path.join(HERE, "examples", name)
+        cmd = ["gcc", "-O2", "-std=gnu11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+               "-I", os.path.join(ROOT, "include"), src, "-L", HERE, "-lhcl", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+               "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        exes.append(exe)
+    return exes
 
 
 if __name__ == "__main__":
     build_lib(force=True, verbose=True)
     print(LIB)
-    print(build_examples(verbose=True))
+    print("\n".join(build_examples(verbose=True)))

@@ -195,6 +195,9 @@ int env_int(const char* name, int dflt) {
   return (v && *v) ? atoi(v) : dflt;
 }
 
+// a reducing step whose segments add up to more than this runs one wavefront x 1 vector per workgroup
+constexpr uint64_t kSmallTileFrom = 512ull << 20;
+
 struct Ctx {
   Ring ring;
   int W = 0;
@@ -214,6 +217,10 @@ struct Ctx {
   int launches = 0;
   bool phase_events = false;  // events at phase boundaries instead of around every launch
   int phases = 0;
+  void* stream2 = nullptr;    // second dependency chain (opts->aux_stream), STEPWISE only
+  bool forked = false;        // stream2 currently waits on / runs ahead of `stream`
+  bool chains_planned = false;
+  uint64_t split_elems = 0;   // elements of a segment before this offset: caller's stream; from it on: stream2
 
   hcl_status_t init(int W_, hcl_dtype_t dt, size_t chunk_bytes, const hcl_opts_t* o, void* st, int op_ = HCL_SUM) {
     opts = o;
@@ -248,6 +255,12 @@ struct Ctx {
     if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
     if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
     phase_events = o && o->events_per_phase;
+    if (o && o->aux_stream) {
+      if (sched != HCL_SCHED_STEPWISE) return fail(HCL_ERR_UNSUPPORTED, "aux_stream: the fused schedule is one launch, there is no chain to split");
+      if (o->aux_stream == st) return fail(HCL_ERR_INVALID_ARG, "aux_stream must differ from the stream of the call");
+      if (!o->aux_events || !o->aux_events[0] || !o->aux_events[1]) return fail(HCL_ERR_INVALID_ARG, "aux_stream needs two events in aux_events");
+      stream2 = o->aux_stream;
+    }
 
     int threads = o && o->threads ? o->threads : env_int("HCL_THREADS", 0);
     int unroll = o && o->unroll ? o->unroll : env_int("HCL_UNROLL", 0);
@@ -275,6 +288,8 @@ struct Ctx {
   // bandwidth on MI355X; starting segment d a few tiles further in removes
   // that.  17 tiles measured best among 0..1025 (anything from 5 to 129 was within 0.3 %).
   static uint32_t stagger_for(uint64_t tiles_per_chunk) {
+    const int forced = env_int("HCL_STAGGER", -1);  // for sweeps
+    if (forced >= 0) return (uint32_t)forced;
     if (tiles_per_chunk > 17) return 17;
     return tiles_per_chunk > 1 ? 1 : 0;
   }
@@ -300,34 +315,128 @@ struct Ctx {
     return HCL_OK;
   }
 
+  // Second dependency chain.  The chunks of a step are independent of each other and chunk j
+  // of one step needs only chunk j of the step before, so the two halves of the chunk range
+  // can run as two chains of launches on two streams: while one chain is between two kernels
+  // (the next one is only dispatched when the last wave of the one before has retired) the
+  // other chain's kernel has the memory system to itself.
+  hcl_status_t fork() {
+    if (forked) return HCL_OK;
+    hipError_t rc = hipEventRecord((hipEvent_t)opts->aux_events[0], (hipStream_t)stream);
+    if (rc == hipSuccess) rc = hipStreamWaitEvent((hipStream_t)stream2, (hipEvent_t)opts->aux_events[0], 0);
+    if (rc != hipSuccess) return fail(HCL_ERR_HIP, "fork onto the second stream: %s", hipGetErrorString(rc));
+    forked = true;
+    return HCL_OK;
+  }
+  hcl_status_t join() {
+    if (!forked) return HCL_OK;
+    forked = false;
+    hipError_t rc = hipEventRecord((hipEvent_t)opts->aux_events[1], (hipStream_t)stream2);
+    if (rc == hipSuccess) rc = hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)opts->aux_events[1], 0);
+    if (rc != hipSuccess) return fail(HCL_ERR_HIP, "join of the second stream: %s", hipGetErrorString(rc));
+    return HCL_OK;
+  }
+  ~Ctx() { (void)join(); }  // an error return between fork and finish() must not leave the streams apart
+
   // Completes the tile grid of a step and launches it.  Empty steps are skipped.
   hcl_status_t launch(StepArgs& a, int nsrc, int ndst) {
     if (a.nseg == 0) return HCL_OK;
+    if (a.nseg > (uint32_t)kMaxSegs) return fail(HCL_ERR_INVALID_ARG, "internal: a step with more than %d segments", kMaxSegs);
     uint64_t maxn = 0;
     for (uint32_t i = 0; i < a.nseg; ++i)
       if (a.seg[i].n > maxn) maxn = a.seg[i].n;
-    uint64_t chunk = (chunk_elems && chunk_elems < maxn) ? chunk_elems : maxn;
-    const uint64_t nchunks = ceil_div(maxn, chunk);
-    Tuning t = tune;
-    // defaults from sweeps on MI355X: reducing steps 128 threads x 2 vectors per source (4 KiB per
-    // source and workgroup), copying steps one wavefront x 1 vector (3 % faster for them)
-    if (nsrc == 1 && auto_threads && auto_unroll) {
-      t.threads = 64;
-      t.unroll = 1;
+    // Which chain an element belongs to must not change during a call: elements before
+    // `split_elems` (a whole number of the caller's chunks, about half of the longest block;
+    // fixed by the first launch of the call, which always holds a full-length block) go to the
+    // caller's stream, the rest to the second one.
+    if (!chains_planned) {
+      chains_planned = true;
+      if (stream2 && chunk_elems && chunk_elems < maxn) split_elems = ceil_div(maxn, chunk_elems) / 2 * chunk_elems;
     }
-    const uint64_t tile = tile_elems(dtype, t);
-    const uint64_t tpc = ceil_div(chunk, tile);
-    const uint64_t total = nchunks * a.nseg * tpc;
-    if (total > 0x7FFFFFFFull) return fail(HCL_ERR_INVALID_ARG, "step needs %llu tiles, more than one launch can index", (unsigned long long)total);
-    a.chunk = chunk;
-    a.tiles_per_chunk = (uint32_t)tpc;
-    a.total_tiles = (uint32_t)total;
-    a.stagger = stagger_for(tpc);
     a.op = nsrc == 2 ? (uint32_t)op : 0u;
-    t.blocks = grid_for(a.total_tiles);
+    Tuning t = tune;
+    // Defaults from sweeps on MI355X.  Copying steps: one wavefront x 1 vector per workgroup.
+    // Reducing steps: 128 threads x 2 vectors per source while one step's output (all ranks
+    // together) is at most twice the 256 MiB last-level cache -- the partial sums one step writes
+    // are what the next one reads -- and one wavefront x 1 vector beyond that, where it measured
+    // 2-5 % faster (W = 16 at 1 GiB per rank, 2 GiB blocks) and far less sensitive to where the
+    // buffers lie in memory.
+    if (auto_threads && auto_unroll) {
+      uint64_t step_bytes = 0;
+      for (uint32_t i = 0; i < a.nseg; ++i) step_bytes += a.seg[i].n * es;
+      if (nsrc == 1 || step_bytes > kSmallTileFrom) {
+        t.threads = 64;
+        t.unroll = 1;
+      }
+    }
+    if (split_elems == 0 || maxn <= split_elems) return launch_range(a, nsrc, ndst, t, 0, maxn, stream);
+    hcl_status_t st = fork();
+    if (st) return st;
+    if ((st = launch_range(a, nsrc, ndst, t, 0, split_elems, stream))) return st;
+    return launch_range(a, nsrc, ndst, t, split_elems, maxn, stream2);
+  }
+
+  // Elements [lo, hi) of every segment of `a`, on stream `on`: as many launches as the tile
+  // index of a launch (31 bits) makes necessary, normally one.
+  hcl_status_t launch_range(const StepArgs& a, int nsrc, int ndst, const Tuning& t, uint64_t lo, uint64_t hi, void* on) {
+    StepArgs b = a;
+    b.nseg = 0;
+    uint64_t maxn = 0;
+    for (uint32_t i = 0; i < a.nseg; ++i) {
+      if (a.seg[i].n <= lo) continue;
+      Seg s = a.seg[i];
+      s.src0 += lo * es;
+      if (s.src1) s.src1 += lo * es;
+      s.dst0 += lo * es;
+      if (s.dst1) s.dst1 += lo * es;
+      s.n = (s.n < hi ? s.n : hi) - lo;
+      if (s.n > maxn) maxn = s.n;
+      b.seg[b.nseg++] = s;
+    }
+    if (b.nseg == 0) return HCL_OK;
+    const uint64_t tile = tile_elems(dtype, t);
+    uint64_t chunk = (chunk_elems && chunk_elems < maxn) ? chunk_elems : maxn;
+    // a chunk only orders the work: a longer one is walked in pieces of 2^20 tiles, so that any
+    // number of chunks can be split over launches of at most 2^31 - 1 tiles each
+    if (chunk > (tile << 20)) chunk = tile << 20;
+    const uint64_t nchunks = ceil_div(maxn, chunk);
+    const uint64_t tpc = ceil_div(chunk, tile);
+    const uint64_t per_launch = 0x7FFFFFFFull / ((uint64_t)b.nseg * tpc);  // chunks one launch can index: >= 63
+    b.chunk = chunk;
+    b.tiles_per_chunk = (uint32_t)tpc;
+    b.stagger = stagger_for(tpc);
+    for (uint64_t c0 = 0; c0 < nchunks; c0 += per_launch) {
+      const uint64_t c1 = c0 + per_launch < nchunks ? c0 + per_launch : nchunks;
+      hcl_status_t st = launch_chunks(b, nsrc, ndst, t, c0, c1, c0 == 0 && c1 == nchunks, on);
+      if (st) return st;
+    }
+    return HCL_OK;
+  }
+
+  // One launch over the chunks [c0, c1) of every segment of `a`.
+  hcl_status_t launch_chunks(const StepArgs& a, int nsrc, int ndst, Tuning t, uint64_t c0, uint64_t c1, bool whole,
+                             void* on) {
+    StepArgs b = a;
+    if (!whole) {
+      const uint64_t lo = c0 * a.chunk, span = (c1 - c0) * a.chunk;
+      b.nseg = 0;
+      for (uint32_t i = 0; i < a.nseg; ++i) {
+        if (a.seg[i].n <= lo) continue;
+        Seg s = a.seg[i];
+        s.src0 += lo * es;
+        if (s.src1) s.src1 += lo * es;
+        s.dst0 += lo * es;
+        if (s.dst1) s.dst1 += lo * es;
+        s.n = s.n - lo < span ? s.n - lo : span;
+        b.seg[b.nseg++] = s;
+      }
+      if (b.nseg == 0) return HCL_OK;
+    }
+    b.total_tiles = (uint32_t)((c1 - c0) * b.nseg * b.tiles_per_chunk);
+    t.blocks = grid_for(b.total_tiles);
     hcl_status_t st = mark(launches);
     if (st) return st;
-    int rc = launch_step(a, dtype, nsrc, ndst, t, stream);
+    int rc = launch_step(b, dtype, nsrc, ndst, t, on);
     if (rc) return fail(HCL_ERR_HIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)rc));
     ++launches;
     return HCL_OK;
@@ -371,7 +480,8 @@ struct Ctx {
   }
 
   hcl_status_t finish() {
-    hcl_status_t st = HCL_OK;
+    hcl_status_t st = join();
+    if (st) return st;
     if (launches) st = phase_events ? record(phases) : record(launches);
     if (opts && opts->n_launches) *opts->n_launches = launches;
     return st;
@@ -380,6 +490,10 @@ struct Ctx {
 
 void add_seg(StepArgs& a, const void* s0, const void* s1, void* d0, void* d1, uint64_t n) {
   if (n == 0) return;
+  if (a.nseg >= (uint32_t)kMaxSegs) {  // cannot happen for W <= 16; Ctx::launch refuses such a step
+    a.nseg = kMaxSegs + 1;
+    return;
+  }
   Seg& s = a.seg[a.nseg++];
   s.src0 = (const char*)s0;
   s.src1 = (const char*)s1;
@@ -430,10 +544,13 @@ struct Inbox {
   char* slot(int rank, int parity) const { return base + ((uint64_t)rank * 2 + (parity & 1)) * slot_bytes; }
 };
 
-// Slots of the workspace and of the pinned inboxes are one block, rounded up to 256 bytes, apart.
-// (A skew between slots, once worth 7 %, stopped paying when the kernels began to stagger the
-// segments' walks: with it the 2 GiB-block Reduce-Scatter measured 63.7 ms, without it 61.3 ms.)
-uint64_t slot_bytes_for(uint64_t block_elems, uint64_t es) { return round_up(block_elems * es, 256); }
+// Slots of the workspace and of the pinned inboxes: one block rounded up to 256 bytes, plus
+// 4 KiB.  With slots exactly one power-of-two block apart, the incoming slot, the local block and
+// the outgoing slot of a step sit at addresses congruent modulo the block size; on some machines
+// (it depends on where the allocation lands physically) that cost the 2 GiB-block Reduce-Scatter
+// 4-7 % of bandwidth, and the 4 KiB took it away; where it cost nothing, the pad changed nothing.
+constexpr uint64_t kSlotPad = 4096;
+uint64_t slot_bytes_for(uint64_t block_elems, uint64_t es) { return round_up(block_elems * es, 256) + kSlotPad; }
 
 hcl_status_t get_inbox(const Ctx& c, uint64_t block_elems, Inbox& ib) {
   if (c.xport != HCL_XPORT_HOST_STAGED) return HCL_OK;
@@ -453,6 +570,52 @@ bool size_overflows(uint64_t count, uint64_t mult, uint64_t es) {
 }
 
 }  // namespace
+
+// ---------------------------------------------------------------------------
+// HCL_DEBUG=1: the call and the work items of its schedule, on stderr
+// ---------------------------------------------------------------------------
+static bool debug_on() {
+  const char* v = getenv("HCL_DEBUG");
+  return v && *v && *v != '0';
+}
+
+// `vec_count`: elements of the full vector the block map cuts (All-Reduce: count; Reduce-Scatter /
+// All-Gather: W * count).  rs / ag: which phases the call runs; ag_first: its first All-Gather step.
+static void debug_call(const char* name, const Ctx& c, uint64_t vec_count, size_t chunk_bytes, bool rs, bool ag,
+                       int ag_first) {
+  static const char* const dt[] = {"fp32", "bf16", "fp16", "int32", "fp64", "int64", "uint8"};
+  static const char* const ops[] = {"sum", "prod", "max", "min"};
+  char ring[8 * kMaxRanks] = "";
+  int ring_i[kMaxRanks];
+  for (int k = 0, at = 0; k < c.W; ++k) {
+    ring_i[k] = c.ring.order[k];
+    at += snprintf(ring + at, sizeof ring - at, k ? " %d" : "%d", ring_i[k]);
+  }
+  fprintf(stderr, "hcl: %s W=%d elements=%llu dtype=%s op=%s chunk_bytes=%zu sched=%s xport=%s%s%s ring=[%s]\n", name, c.W,
+          (unsigned long long)vec_count, dt[c.dtype], ops[c.op], chunk_bytes, c.sched == HCL_SCHED_FUSED ? "fused" : "stepwise",
+          c.xport == HCL_XPORT_HOST_STAGED ? "host_staged" : "direct", c.fuse_rs_ag ? " fuse_rs_ag" : "",
+          c.stream2 ? " two_chains" : "", ring);
+  if (c.W < 2 || c.sched != HCL_SCHED_STEPWISE) return;
+  const size_t cap = (size_t)env_int("HCL_DEBUG_ITEMS", 64);  // items printed per step
+  hcl_work_item_t* items = (hcl_work_item_t*)malloc((cap ? cap : 1) * sizeof(hcl_work_item_t));
+  if (!items) return;
+  for (int phase = 0; phase < 2; ++phase) {
+    if (!(phase == HCL_PHASE_RS ? rs : ag)) continue;
+    for (int s = phase == HCL_PHASE_AG ? ag_first : 0; s <= c.W - 2; ++s) {
+      size_t n = 0;
+      if (hcl_schedule_items(c.W, ring_i, vec_count, (hcl_dtype_t)c.dtype, chunk_bytes, phase, s, items, cap, &n) != HCL_OK) break;
+      fprintf(stderr, "hcl:  %s step %d: %zu work items\n", phase == HCL_PHASE_RS ? "reduce-scatter" : "all-gather", s, n);
+      for (size_t i = 0; i < n && i < cap; ++i) {
+        const hcl_work_item_t& it = items[i];
+        fprintf(stderr, "hcl:   rank %d <- rank %d: block %d chunk %llu, elements [%llu, %llu) of the vector%s; passes on block %d\n",
+                it.rank, it.from_rank, it.block, (unsigned long long)it.chunk, (unsigned long long)it.vec_offset,
+                (unsigned long long)(it.vec_offset + it.elem_count), phase == HCL_PHASE_RS ? ", reduced" : ", copied", it.send_block);
+      }
+      if (n > cap) fprintf(stderr, "hcl:   ... and %zu more\n", n - cap);
+    }
+  }
+  free(items);
+}
 
 // ---------------------------------------------------------------------------
 // workspace queries
@@ -629,6 +792,7 @@ extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* 
   Range extra[1] = {{ib.base, ib.slot_bytes * 2 * W}};
   if ((st = check_alias(send, recv, W, bytes, bytes, extra, ib.base ? 1 : 0, inplace, false))) return st;
 
+  if (debug_on()) debug_call("all-reduce", c, count, chunk_bytes, true, true, (c.fuse_rs_ag && c.xport == HCL_XPORT_DIRECT) ? 1 : 0);
   if (W == 1) {
     if ((st = c.phase())) return st;
     if ((st = copy_all(c, send, recv, count))) return st;
@@ -690,6 +854,7 @@ extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* co
   // a staged in-place ring never writes partials into send[], a direct one does
   if ((st = check_alias(send, recv, W, n * W * es, n * es, extra, 2, inplace, inplace && stepwise_direct))) return st;
 
+  if (debug_on()) debug_call("reduce-scatter", c, n * W, chunk_bytes, true, false, 0);
   if (W == 1) {
     if ((st = c.phase())) return st;
     if ((st = copy_all(c, send, recv, n))) return st;
@@ -733,6 +898,7 @@ extern "C" hcl_status_t hcl_all_gather_sim(const void* const* send, void* const*
   Range extra[1] = {{ib.base, ib.slot_bytes * 2 * W}};
   if ((st = check_alias(send, recv, W, n * es, n * W * es, extra, 1, inplace, false))) return st;
 
+  if (debug_on()) debug_call("all-gather", c, n * W, chunk_bytes, false, true, 0);
   if (c.sched == HCL_SCHED_FUSED) {
     FusedArgs f;
     fill_fused(c, f, send, recv, n * W, n, 2);

@@ -1,10 +1,10 @@
 // Ring chunk scheduler: host-only integer logic (no HIP types).
 //
-// The paper reuses the vendor libraries' "host-side logic for partitioning and
-// communicating data" as a black box (Section 4.2); this is that logic for the
-// textbook ring, written out: which block every rank sends and receives at
-// every step, where a block sits in the vector, and how a block is cut into
-// chunks.
+// The paper takes the vendor libraries' host side -- how a message is cut up
+// and which piece moves when -- as a black box (Section 4.2); this is that
+// logic for the textbook ring, written out: which block every rank sends and
+// receives at every step, where a block sits in the vector, and how a block is
+// cut into chunks.
 #pragma once
 #include <cstddef>
 #include <cstdint>

@@ -68,6 +68,8 @@ class Opts(ctypes.Structure):
         ("n_launches", ctypes.POINTER(ctypes.c_int)),
         ("accumulate", ctypes.c_int),
         ("order", ctypes.c_int),
+        ("aux_stream", ctypes.c_void_p),
+        ("aux_events", ctypes.POINTER(ctypes.c_void_p)),
     ]
 
 
@@ -174,7 +176,7 @@ class EventList:
 
 def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, host_stage=None,
               threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None,
-              events_per_phase=False, accumulate=0, order=0):
+              events_per_phase=False, accumulate=0, order=0, aux_stream=None, aux_events=None):
     """Builds the hcl_opts_t struct.  Returns (opts, keepalive): keep `keepalive`
     referenced until the call has returned."""
     o = Opts()
@@ -206,6 +208,12 @@ def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, ho
         o.n_events = n
         o.events_per_phase = 1 if events_per_phase else 0
         keep.append(ev)
+    if aux_stream is not None:
+        # a torch stream and an EventList of two events: the second dependency chain
+        o.aux_stream = aux_stream.cuda_stream
+        assert aux_events is not None and aux_events.n >= 2
+        o.aux_events = ctypes.cast(aux_events.arr, ctypes.POINTER(ctypes.c_void_p))
+        keep += [aux_stream, aux_events]
     nl = ctypes.c_int(0)
     o.n_launches = ctypes.pointer(nl)
     keep.append(nl)

@@ -78,6 +78,25 @@ def test_allreduce_validation_codes():
     assert "overflow" in hcl.lib().hcl_last_error().decode()
 
 
+def test_second_stream_validation():
+    """aux_stream: STEPWISE only, distinct from the call's stream, two events alongside."""
+    s, r = bufs(4), bufs(4, base=BASE * 2)
+    ps, pr = (ctypes.c_void_p * 4)(*s), (ctypes.c_void_p * 4)(*r)
+    ev = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+
+    def call(sched, aux, events, stream=None, count=16):
+        o, keep = hcl.make_opts(4, sched=sched)
+        o.aux_stream = aux
+        o.aux_events = ctypes.cast(events, ctypes.POINTER(ctypes.c_void_p)) if events is not None else None
+        return hcl.lib().hcl_allreduce_sim(ps, pr, 4, count, hcl.FP32, hcl.SUM, 0, ctypes.byref(o), stream)
+
+    assert call("fused", 0x5000, ev) == hcl.ERR_UNSUPPORTED
+    assert call("stepwise", 0x5000, None) == hcl.ERR_INVALID_ARG
+    assert call("stepwise", 0x5000, (ctypes.c_void_p * 2)(0x1000, 0)) == hcl.ERR_INVALID_ARG
+    assert call("stepwise", 0x5000, ev, stream=0x5000) == hcl.ERR_INVALID_ARG
+    assert call("stepwise", 0x5000, ev, count=0) == hcl.OK              # nothing to do, nothing forked
+
+
 def test_allreduce_alias_rules():
     s = bufs(4)
     # partially in place
@@ -112,8 +131,8 @@ def test_staging_and_workspace_rules():
 
 def test_workspace_and_host_stage_sizes():
     # out-of-place stepwise reduce-scatter: two slots per rank, each one block rounded up to
-    # 256 bytes
-    skew = 0
+    # 256 bytes plus 4 KiB (so that slots are not a power of two apart)
+    skew = 4096
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * 2 * ((1 << 21) + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * 2 * (512 + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 2, 1 << 20, hcl.BF16) == 0
@@ -212,6 +231,6 @@ def test_other_collectives_validation_codes():
     assert L.hcl_alltoall_sim(ps, ps, 4, 16, hcl.FP32, 0, ctypes.byref(o), None) == hcl.ERR_ALIAS
     pr_null = (ctypes.c_void_p * 4)(None, r[1], r[2], r[3])
     assert L.hcl_reduce_sim(ps, pr_null, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * (1 << 21)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * ((1 << 21) + 4096)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16, sched="fused") == 0
     assert hcl.workspace_bytes(hcl.KIND_BROADCAST, 8, 1 << 20, hcl.BF16) == 0

@@ -206,7 +206,7 @@ def test_config5_named_size_host_staged_every_element():
     send = _device_inputs(5, W, count, dtype, c["dist"])
     recv = [torch.zeros_like(t) for t in send]
     nb = hcl.host_stage_bytes(hcl.KIND_ALLREDUCE, W, count, code, chunk, xport="host_staged")
-    assert nb == 2 * W * (64 << 20)
+    assert nb == 2 * W * ((64 << 20) + 4096)
     stage = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
     assert hcl.allreduce_sim(send, recv, chunk_bytes=chunk, xport="host_staged", host_stage=stage) == 2 * (W - 1) + 1
     torch.cuda.synchronize()

@@ -230,3 +230,54 @@ def test_single_hop_over_all_bit_patterns(dtype):
     for sched in ("stepwise", "fused"):
         run_allreduce(0, 2, a.numel(), dtype, None, cpu_inputs=[a, b], sched=sched)
         run_allreduce(0, 2, a.numel(), dtype, None, cpu_inputs=[b, a], sched=sched, misalign=1)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "int32"])
+def test_two_dependency_chains_give_the_same_bits(dtype):
+    """opts.aux_stream: the second half of every step's chunks runs as a chain of its own on a
+    second stream.  Every collective of the stepwise schedule, both transports, in and out of
+    place, ragged blocks, chunk counts that are odd, one and two."""
+    s2, ev = torch.cuda.Stream(), hcl.EventList(2)
+    es = wl.ESIZE[dtype]
+    kw = dict(aux_stream=s2, aux_events=ev)
+    for k, (W, count, ring, chunk) in enumerate([(8, 1_000_003, None, 16 * 1024), (5, 262_147, [3, 1, 4, 0, 2], 4096),
+                                                 (4, 300_000, None, es * 25_000), (16, 2_000_003, None, 64 * 1024),
+                                                 (3, 100_000, None, es * 40_000), (2, 50_001, None, 0)]):
+        for inplace in (False, True):
+            n = run_allreduce(800 + k, W, count, dtype, DIST[dtype], ring=ring, chunk_bytes=chunk, inplace=inplace, **kw)
+            B = -(-count // W)
+            nch = -(-B * es // chunk) if chunk else 1
+            assert n == 2 * (W - 1) * (2 if nch >= 2 else 1), (n, W, nch)
+            run_allreduce(810 + k, W, count, dtype, DIST[dtype], ring=ring, chunk_bytes=chunk, inplace=inplace,
+                          fuse_rs_ag=True, **kw)
+    for inplace in (False, True):
+        run_allreduce(820, 8, 500_003, dtype, DIST[dtype], chunk_bytes=32 * 1024, inplace=inplace, xport="host_staged", **kw)
+        run_reduce_scatter(821, 8, 125_003, dtype, DIST[dtype], chunk_bytes=8192, inplace=inplace, **kw)
+        run_all_gather(822, 8, 125_003, dtype, DIST[dtype], chunk_bytes=8192, inplace=inplace, **kw)
+        run_reduce_scatter(823, 4, 30_001, dtype, DIST[dtype], chunk_bytes=4096, inplace=inplace, xport="host_staged", **kw)
+    ev.close()
+
+
+def test_two_dependency_chains_under_graph_capture():
+    """The fork onto the second stream and the join back are event record / wait pairs, so a call
+    with aux_stream can be captured from the caller's stream; replays must reproduce the result."""
+    W, count, dtype = 4, 600_000, "bf16"
+    cpu, dev = device_inputs(830, W, count, dtype, DIST[dtype])
+    want = orc.allreduce([wl.to_wire(t) for t in cpu], CODE[dtype])
+    recv = fresh(W, count, dtype, fill=0)
+    s2, ev = torch.cuda.Stream(), hcl.EventList(2)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        n = hcl.allreduce_sim(dev, recv, chunk_bytes=32768, aux_stream=s2, aux_events=ev)
+    assert n == 4 * (W - 1)
+    for rep in range(3):
+        for t in recv:
+            t.fill_(float(rep))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for r in range(W):
+            assert_same_bits(recv[r], want[r], dtype, f"two chains, graph replay {rep} rank {r}")
+    del g
+    ev.close()

@@ -22,6 +22,16 @@ DIST = {"fp32": ("uniform", -2.0, 2.0), "bf16": ("normal", 0.0, 1.0), "fp16": ("
         "uint8": ("randint", 0, 255)}
 
 
+_CHAIN = []
+
+
+def _second_chain():
+    """One side stream and one pair of events for every call that wants two chains."""
+    if not _CHAIN:
+        _CHAIN.extend([torch.cuda.Stream(), hcl.EventList(2)])
+    return _CHAIN[0], _CHAIN[1]
+
+
 def _case(rnd):
     dtype = rnd.choice(list(DIST))
     es = wl.ESIZE[dtype]
@@ -38,6 +48,8 @@ def _case(rnd):
     c["fuse"] = sched == "stepwise" and c["kind"] == "allreduce" and rnd.random() < 0.3
     # blocks travelling through pinned host memory: STEPWISE All-Reduce and Reduce-Scatter have that transport
     c["xport"] = "host_staged" if (sched == "stepwise" and c["kind"] != "reduce" and rnd.random() < 0.3) else "direct"
+    # the chunk range split over two streams, each half a dependency chain of its own
+    c["two_chains"] = sched == "stepwise" and rnd.random() < 0.35
     n = rnd.choice([1, 17, 1000, 4096, 65_536, rnd.randrange(1, 200_000)])
     c["n"] = n
     chunk_elems = rnd.choice([0, 0, 1, 16, 1024, 8192, rnd.randrange(1, 50_000)])
@@ -56,6 +68,8 @@ def _run(c, seed):
                accumulate=c["acc"], threads=c["threads"], unroll=c["unroll"], blocks=c["blocks"],
                nontemporal=c["nontemporal"], xport=c["xport"])
     tag = f"seed {seed}: {c}"
+    if c["two_chains"]:
+        opt["aux_stream"], opt["aux_events"] = _second_chain()
     if c["xport"] == "host_staged":
         kind = hcl.KIND_ALLREDUCE if c["kind"] == "allreduce" else hcl.KIND_REDUCE_SCATTER
         opt["host_stage"] = pinned_stage(hcl.host_stage_bytes(kind, W, n, code, c["chunk"], xport="host_staged"))

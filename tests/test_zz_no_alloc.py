@@ -43,7 +43,7 @@ def test_static_scratch_reduce_scatter_two_calls_in_a_row():
 def test_static_scratch_limit_and_forms_that_need_no_scratch():
     W, dtype = 4, "int32"
     limit = hcl.static_scratch_bytes()
-    n_max = limit // (2 * W) // 4                      # largest block whose 2 W slots fit
+    n_max = (limit // (2 * W) - 4096) // 4             # largest block whose 2 W slots (block + 4 KiB each) fit
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n_max, CODE[dtype]) == limit
     cpu, dev = device_inputs(903, W, W * (n_max + 64), dtype, ("randint", -1000, 1000))
     out = fresh(W, n_max + 64, dtype, fill=0)
