@@ -156,7 +156,11 @@ typedef struct hcl_opts {
                               Broadcast 1, or 4 for blocks of 1 GiB
                               and more), else 1, 2, 4 or 8 (8: step kernels only).  The FUSED
                               reductions always keep one vector per thread and rank           */
-  int nontemporal;         /* 0 = default (streaming stores), 1 = on, -1 = off              */
+  int nontemporal;         /* cache policy of the memory accesses.  0 = default: non-temporal
+                              (streaming) loads; STEPWISE stores are regular while one step's
+                              output fits the 256 MiB last-level cache (the next step reads it) and
+                              non-temporal beyond; FUSED stores are non-temporal.  1 = loads and
+                              stores non-temporal, 2 = loads only, -1 = neither                  */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the
                               first All-Gather step is dropped (same bits, one read fewer)   */
@@ -234,7 +238,7 @@ hcl_status_t hcl_reduce_scatter_sim(const void *const *send, void *const *recv, 
  * part of the library's code object -- every GPU the process uses holds one copy
  * until the process ends.  The call allocates and frees nothing.  A call whose
  * partial sums need more than that (hcl_workspace_bytes(HCL_KIND_REDUCE_SCATTER,
- * ...) > HCL_STATIC_SCRATCH_BYTES, i.e. blocks beyond 32 MiB / (2 W)) returns
+ * ...) > HCL_STATIC_SCRATCH_BYTES, i.e. blocks beyond about 32 MiB / W) returns
  * HCL_ERR_WORKSPACE and launches nothing.  Nothing in the array has to be
  * cleared between calls (each partial is written before it is read), but all
  * calls on one GPU share it: two such calls may not overlap in time on the same
@@ -264,7 +268,7 @@ hcl_status_t hcl_all_gather_sim(const void *const *send, void *const *recv, int 
  * chain ends at the root: the reduction runs in the order next(root), ..., root, i.e.
  * as block `root` of the All-Reduce does.  In place: recv[root] == send[root].
  * STEPWISE (W - 1 launches) with W > 2 keeps the travelling partial in
- * opts->workspace (hcl_workspace_bytes with HCL_KIND_REDUCE: two slots of the
+ * opts->workspace (hcl_workspace_bytes with HCL_KIND_REDUCE: one slot of the
  * vector); FUSED is one launch and needs none.  DIRECT transport only.
  */
 hcl_status_t hcl_reduce_sim(const void *const *send, void *const *recv, int W, size_t count,
@@ -298,10 +302,12 @@ hcl_status_t hcl_alltoall_sim(const void *const *send, void *const *recv, int W,
  * travelling partial sums live when they can live in neither send[] nor recv[]
  * (the library's counterpart of the vendor library's internal buffers, Section
  * 4.2).  `count` is the count argument of that kind's entry point.
- *   - STEPWISE, DIRECT Reduce-Scatter with W > 2: 2 * W slots; the figure is the
- *     out-of-place one (the in-place form keeps its partial sums in send[] and
- *     ignores the workspace; this query cannot know which form the call will be).
- *   - STEPWISE Reduce with W > 2: 2 slots.
+ *   - STEPWISE, DIRECT Reduce-Scatter with W > 2: W slots, one per block, in
+ *     which the block's travelling partial sum is read, combined and written
+ *     back step after step; the figure is the out-of-place one (the in-place
+ *     form keeps its partial sums in send[] and ignores the workspace; this
+ *     query cannot know which form the call will be).
+ *   - STEPWISE Reduce with W > 2: 1 slot.
  *   - everything else: 0.
  * A slot is one block (Reduce: the vector) rounded up to 256 bytes, plus 4 KiB.
  * opts->workspace must be 16-byte aligned.  Returns 0 on invalid arguments too. */

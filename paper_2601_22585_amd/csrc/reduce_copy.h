@@ -57,7 +57,8 @@ struct Tuning {
   int threads;      // per workgroup, multiple of 64
   int blocks;       // workgroups
   int unroll;       // 1, 2, 4, 8
-  bool nontemporal;
+  int nt;           // cache policy: 0 regular loads and stores; 1 non-temporal (streaming) loads, regular
+                    // stores; 2 non-temporal loads and stores.  The fused kernels know on (!= 0) and off
 };
 
 // Elements one tile covers for this dtype / tuning.

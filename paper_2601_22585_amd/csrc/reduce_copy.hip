@@ -16,8 +16,12 @@ namespace hcl {
 // STEPWISE: one ring step of every rank.  128-bit path.
 // ---------------------------------------------------------------------------
 // GEN: the operator is a.op at run time (product, maximum, minimum); otherwise the sum.
-template <int DT, int NSRC, int NDST, int UNROLL, bool NT, bool GEN>
+// NT: 0 regular loads and stores; 1 non-temporal loads, regular stores -- what a step writes stays
+// in the 256 MiB last-level cache for the next step, which reads it as its incoming operand;
+// 2 non-temporal loads and stores, for outputs that exceed that cache anyway.
+template <int DT, int NSRC, int NDST, int UNROLL, int NT, bool GEN>
 __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
+  constexpr bool NTL = NT >= 1, NTS = NT == 2;
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
   constexpr uint32_t VE = 16 / ES;
@@ -40,15 +44,15 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) {
         const uint32_t off = (u * nthr + tid) * 16u;
-        v0[u] = ld16<NT>(s0 + off);
-        if (NSRC == 2) v1[u] = ld16<NT>(s1 + off);
+        v0[u] = ld16<NTL>(s0 + off);
+        if (NSRC == 2) v1[u] = ld16<NTL>(s1 + off);
       }
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) {
         const uint32_t off = (u * nthr + tid) * 16u;
         const u32x4 r = NSRC == 2 ? (GEN ? op_vec<DT>(a.op, v0[u], v1[u]) : hop_vec<DT>(v0[u], v1[u])) : v0[u];
-        st16<NT>(d0 + off, r);
-        if (NDST == 2) st16<NT>(d1 + off, r);
+        st16<NTS>(d0 + off, r);
+        if (NDST == 2) st16<NTS>(d1 + off, r);
       }
     } else {
       const uint32_t nvec = len / VE;
@@ -57,10 +61,10 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
         const uint32_t vi = u * nthr + tid;
         if (vi < nvec) {
           const uint32_t off = vi * 16u;
-          u32x4 r = ld16<NT>(s0 + off);
-          if (NSRC == 2) r = GEN ? op_vec<DT>(a.op, r, ld16<NT>(s1 + off)) : hop_vec<DT>(r, ld16<NT>(s1 + off));
-          st16<NT>(d0 + off, r);
-          if (NDST == 2) st16<NT>(d1 + off, r);
+          u32x4 r = ld16<NTL>(s0 + off);
+          if (NSRC == 2) r = GEN ? op_vec<DT>(a.op, r, ld16<NTL>(s1 + off)) : hop_vec<DT>(r, ld16<NTL>(s1 + off));
+          st16<NTS>(d0 + off, r);
+          if (NDST == 2) st16<NTS>(d1 + off, r);
         }
       }
       // fewer than VE elements may remain at the very end of a segment
@@ -92,8 +96,9 @@ static int launch_step_vec(const StepArgs& a, const Tuning& t, hipStream_t s) {
   const dim3 g(t.blocks), b(t.threads);
 #define HCL_CASE(U)                                                                          \
   case U:                                                                                    \
-    if (t.nontemporal) reduce_copy_vec<DT, NSRC, NDST, U, true, GEN><<<g, b, 0, s>>>(a);     \
-    else reduce_copy_vec<DT, NSRC, NDST, U, false, GEN><<<g, b, 0, s>>>(a);                  \
+    if (t.nt == 2) reduce_copy_vec<DT, NSRC, NDST, U, 2, GEN><<<g, b, 0, s>>>(a);            \
+    else if (t.nt == 1) reduce_copy_vec<DT, NSRC, NDST, U, 1, GEN><<<g, b, 0, s>>>(a);       \
+    else reduce_copy_vec<DT, NSRC, NDST, U, 0, GEN><<<g, b, 0, s>>>(a);                      \
     break;
   switch (t.unroll) {
     HCL_CASE(1) HCL_CASE(2) HCL_CASE(4) HCL_CASE(8)

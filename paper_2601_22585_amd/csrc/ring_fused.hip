@@ -354,7 +354,7 @@ int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
     constexpr int ES = sizeof(typename Wire<DT>::elem_t);
 #define HCL_CASE(UU)                                                            \
   case UU:                                                                      \
-    if (t.nontemporal) gather_fused_vec<ES, true, UU><<<g, b, 0, s>>>(a);       \
+    if (t.nt) gather_fused_vec<ES, true, UU><<<g, b, 0, s>>>(a);       \
     else gather_fused_vec<ES, false, UU><<<g, b, 0, s>>>(a);                    \
     break;
     switch (t.unroll) {
@@ -369,10 +369,10 @@ int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
 #define HCL_CASE(WW)                                                                      \
   case WW:                                                                                \
     if (wide) {                                                                           \
-      if (t.nontemporal) ring_fused_vec<DT, WW, true, kW><<<g, b, 0, s>>>(a);             \
+      if (t.nt) ring_fused_vec<DT, WW, true, kW><<<g, b, 0, s>>>(a);             \
       else ring_fused_vec<DT, WW, false, kW><<<g, b, 0, s>>>(a);                          \
     } else {                                                                              \
-      if (t.nontemporal) ring_fused_vec<DT, WW, true, false><<<g, b, 0, s>>>(a);          \
+      if (t.nt) ring_fused_vec<DT, WW, true, false><<<g, b, 0, s>>>(a);          \
       else ring_fused_vec<DT, WW, false, false><<<g, b, 0, s>>>(a);                       \
     }                                                                                     \
     break;
@@ -393,7 +393,7 @@ int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream) {
   if (t.threads > kGenMaxThreads) return (int)hipErrorInvalidValue;
 #define HCL_CASE(WW)                                                              \
   case WW:                                                                        \
-    if (t.nontemporal) ring_fused_gen<DT, WW, true><<<g, b, 0, s>>>(a);           \
+    if (t.nt) ring_fused_gen<DT, WW, true><<<g, b, 0, s>>>(a);           \
     else ring_fused_gen<DT, WW, false><<<g, b, 0, s>>>(a);                        \
     break;
   switch (a.W) {

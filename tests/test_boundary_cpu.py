@@ -73,7 +73,7 @@ def test_allreduce_validation_codes():
     assert _call_ar(s, r, 4, 16, xport=5) == hcl.ERR_UNSUPPORTED
     assert _call_ar(s, r, 4, 16, threads=100) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 16, unroll=3) == hcl.ERR_INVALID_ARG
-    assert _call_ar(s, r, 4, 16, nontemporal=2) == hcl.ERR_INVALID_ARG
+    assert _call_ar(s, r, 4, 16, nontemporal=3) == hcl.ERR_INVALID_ARG
     assert _call_ar(s, r, 4, 2**62) == hcl.ERR_INVALID_ARG                 # byte size overflows
     assert "overflow" in hcl.lib().hcl_last_error().decode()
 
@@ -130,11 +130,11 @@ def test_staging_and_workspace_rules():
 
 
 def test_workspace_and_host_stage_sizes():
-    # out-of-place stepwise reduce-scatter: two slots per rank, each one block rounded up to
+    # out-of-place stepwise reduce-scatter: one slot per block, each one block rounded up to
     # 256 bytes plus 4 KiB (so that slots are not a power of two apart)
     skew = 4096
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * 2 * ((1 << 21) + skew)
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * 2 * (512 + skew)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16) == 8 * ((1 << 21) + skew)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 100, hcl.FP32) == 8 * (512 + skew)
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 2, 1 << 20, hcl.BF16) == 0
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, 8, 1 << 20, hcl.BF16, sched="fused") == 0
     assert hcl.workspace_bytes(hcl.KIND_ALLREDUCE, 8, 1 << 20, hcl.BF16) == 0
@@ -231,6 +231,6 @@ def test_other_collectives_validation_codes():
     assert L.hcl_alltoall_sim(ps, ps, 4, 16, hcl.FP32, 0, ctypes.byref(o), None) == hcl.ERR_ALIAS
     pr_null = (ctypes.c_void_p * 4)(None, r[1], r[2], r[3])
     assert L.hcl_reduce_sim(ps, pr_null, 4, 16, hcl.FP32, hcl.SUM, 0, 0, ctypes.byref(o), None) == hcl.ERR_INVALID_ARG
-    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == 2 * ((1 << 21) + 4096)
+    assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16) == (1 << 21) + 4096
     assert hcl.workspace_bytes(hcl.KIND_REDUCE, 8, 1 << 20, hcl.BF16, sched="fused") == 0
     assert hcl.workspace_bytes(hcl.KIND_BROADCAST, 8, 1 << 20, hcl.BF16) == 0

@@ -121,7 +121,7 @@ def test_host_staged_transport(dtype):
 def test_launch_shapes_do_not_change_the_bits():
     W, count, dtype = 8, 600_011, "bf16"
     for kw in [dict(threads=64, unroll=1), dict(threads=1024, unroll=8), dict(blocks=1), dict(blocks=7, unroll=2),
-               dict(nontemporal=-1), dict(threads=512, unroll=4, blocks=3000)]:
+               dict(nontemporal=-1), dict(nontemporal=1), dict(nontemporal=2), dict(threads=512, unroll=4, blocks=3000)]:
         for sched in ("stepwise", "fused"):
             run_allreduce(500, W, count, dtype, DIST[dtype], chunk_bytes=32 * 1024, sched=sched, **kw)
 

@@ -42,7 +42,7 @@ def _case(rnd):
              ring=None if rnd.random() < 0.4 else rnd.sample(range(W), W),
              mis=rnd.choice([0, 0, 0, 1, 3]), inplace=rnd.random() < 0.3,
              threads=rnd.choice([0, 0, 64, 128, 256, 1024]), unroll=rnd.choice([0, 0, 1, 2, 4, 8]),
-             blocks=rnd.choice([0, 0, 0, 7, 64, 1000]), nontemporal=rnd.choice([0, 0, -1]))
+             blocks=rnd.choice([0, 0, 0, 7, 64, 1000]), nontemporal=rnd.choice([0, 0, -1, 1, 2]))
     c["order"] = rnd.choice(["ring", "tree"]) if sched == "fused" else "ring"
     c["acc"] = rnd.choice(["per_hop", "fp32"]) if sched == "fused" else "per_hop"
     c["fuse"] = sched == "stepwise" and c["kind"] == "allreduce" and rnd.random() < 0.3

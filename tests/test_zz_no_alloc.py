@@ -35,7 +35,7 @@ def _both(seed, W, n, dtype, dist, chunk_bytes, ring=None):
 
 def test_static_scratch_reduce_scatter_two_calls_in_a_row():
     # the first call fills nearly all of the array, the second reuses its head with other data
-    _both(900, 8, 1_000_003, "bf16", ("normal", 0.0, 1e-3), 64 * 1024)
+    _both(900, 8, 2_000_003, "bf16", ("normal", 0.0, 1e-3), 64 * 1024)
     _both(901, 5, 70_001, "fp32", ("uniform", -1.0, 1.0), 0, ring=[3, 0, 4, 1, 2])
     _both(902, 16, 9, "fp16", ("normal", 0.0, 1.0), 0)
 
@@ -43,7 +43,7 @@ def test_static_scratch_reduce_scatter_two_calls_in_a_row():
 def test_static_scratch_limit_and_forms_that_need_no_scratch():
     W, dtype = 4, "int32"
     limit = hcl.static_scratch_bytes()
-    n_max = (limit // (2 * W) - 4096) // 4             # largest block whose 2 W slots (block + 4 KiB each) fit
+    n_max = (limit // W - 4096) // 4                   # largest block whose W slots (block + 4 KiB each) fit
     assert hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n_max, CODE[dtype]) == limit
     cpu, dev = device_inputs(903, W, W * (n_max + 64), dtype, ("randint", -1000, 1000))
     out = fresh(W, n_max + 64, dtype, fill=0)
