@@ -222,6 +222,7 @@ struct Ctx {
   int phases = 0;
   void* stream2 = nullptr;    // second dependency chain (opts->aux_stream), STEPWISE only
   bool forked = false;        // stream2 currently waits on / runs ahead of `stream`
+  int steps_issued = 0;       // step launches so far: odd ones walk their tiles backwards
   bool chains_planned = false;
   uint64_t split_elems = 0;   // elements of a segment before this offset: caller's stream; from it on: stream2
 
@@ -359,6 +360,10 @@ struct Ctx {
       if (stream2 && chunk_elems && chunk_elems < maxn) split_elems = ceil_div(maxn, chunk_elems) / 2 * chunk_elems;
     }
     a.op = nsrc == 2 ? (uint32_t)op : 0u;
+    // Consecutive steps walk their tiles in opposite directions: the end of what one step wrote is
+    // what the last-level cache still holds when the next step starts (+1.5 % at 256 MiB per rank,
+    // where one step's output is as large as that cache; neutral elsewhere).
+    a.reverse = (uint32_t)(steps_issued++ & 1);
     Tuning t = tune;
     // Defaults from sweeps on MI355X.  Copying steps: one wavefront x 1 vector per workgroup.
     // Reducing steps: 128 threads x 2 vectors per source while one step's output (all ranks

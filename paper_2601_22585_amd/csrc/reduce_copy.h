@@ -30,7 +30,7 @@ struct StepArgs {
   uint32_t stagger;  // segment d starts its walk through a chunk d * stagger tiles in (mod tiles_per_chunk)
   uint64_t chunk;    // elements per chunk (> 0)
   uint32_t op;       // NSRC = 2: 0 sum, 1 product, 2 maximum, 3 minimum
-  uint32_t pad_;
+  uint32_t reverse;  // 1: the tiles are walked from the last to the first
 };
 
 // Whole-collective launch: every element's ring pass stays in one thread.

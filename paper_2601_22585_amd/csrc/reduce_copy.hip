@@ -28,7 +28,10 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * UNROLL;
 
-  for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+  for (uint32_t t0 = blockIdx.x; t0 < a.total_tiles; t0 += gridDim.x) {
+    // consecutive steps walk the tiles in opposite directions: what the step before wrote last
+    // is what the last-level cache still holds, so it is read first
+    const uint32_t t = a.reverse ? a.total_tiles - 1u - t0 : t0;
     const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile, a.stagger);
     const uint32_t len = tile_len(p, a.seg[p.d].n, a.chunk, tile);
     if (len == 0) continue;
