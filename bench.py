@@ -105,6 +105,8 @@ def parse():
                     help="give every rank buffer an allocation of its own instead of carving all of them out of one")
     ap.add_argument("--chains", type=int, default=1, choices=[1, 2],
                     help="2: stepwise schedule with the chunk range split over two streams (opts.aux_stream)")
+    ap.add_argument("--slab-bytes", type=int, default=0,
+                    help="opts.slab_bytes: 0 = library default (a step's output per slab fits the last-level cache), -1 = no slabs")
     ap.add_argument("--no-cache-free-probe", action="store_true",
                     help="default workload only: skip the extra measurement of the dominant kernel at a footprint far beyond the last-level cache")
     return ap.parse_args()
@@ -193,6 +195,8 @@ def main():
 
     opt = dict(sched=args.sched, xport=xport, threads=args.threads, blocks=args.blocks, unroll=args.unroll,
                nontemporal=args.nontemporal)
+    if args.slab_bytes:
+        opt["slab_bytes"] = args.slab_bytes
     if args.accumulate != "per_hop":
         opt["accumulate"] = args.accumulate
     if args.order != "ring":
@@ -414,8 +418,31 @@ def main():
         call_bytes = 3 * (W - 1) * S
         if op == "allreduce":
             call_bytes = 5 * (W - 1) * S - (S if fuse else 0)
+    # slabs (opts.slab_bytes): the library runs the whole ring on one slab of every block before the
+    # next, so a "step" of the ring is n_slabs launches, each moving 1 / n_slabs of the step's bytes
+    n_slabs = 1
+    if args.sched == "stepwise" and not staged and op != "alltoall" and args.slab_bytes >= 0:
+        budget = args.slab_bytes or (256 << 20)
+        one_block = op in ("reduce", "broadcast")
+        gran = chunk_bytes // es if chunk_bytes else 65536
+        slab = max(gran, budget // ((1 if one_block else W) * es) // gran * gran)
+        n_slabs = max(1, -(-(count if one_block else B) // slab))
+    bytes_per_launch /= n_slabs
+    units *= n_slabs
+    n_dom *= n_slabs
+    if n_slabs > 1:
+        dom = list(range(launches))
     roof = None
-    if ev is not None:
+    if ev is not None and n_slabs > 1 and op == "allreduce":
+        # with several slabs the Reduce-Scatter and All-Gather launches of a call interleave: there is
+        # no phase to bracket, the figure is the whole call's
+        achieved = call_bytes / (ms_per_step * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": f"reduce_copy_vec<{dtype},NSRC=2,NDST=1> and reduce_copy_vec<copy,NSRC=1,NDST=1>, every launch of the call",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None, "bytes_per_launch": int(call_bytes / launches), "avg_launch_ms": round(ms_per_step / launches, 5),
+                "launches_timed": K * launches, "timing": f"whole call / launches ({n_slabs} slabs: the phases interleave)"}
+        ev.close()
+    elif ev is not None:
         if phase_mode:
             # phase 0 holds the dominant kernel's launches; launches of another shape in the same
             # phase (fused last RS step, staged pre-step, own-shard copy) count by their share of bytes
@@ -479,13 +506,14 @@ def main():
         reps = 3
         pev = hcl.EventList(2 * (reps + 1))
         for k in range(reps + 1):
-            hcl.reduce_scatter_sim(big, shards, chunk_bytes=c4["chunk_bytes"], stream=stream,
+            hcl.reduce_scatter_sim(big, shards, chunk_bytes=c4["chunk_bytes"], stream=stream, slab_bytes=-1,
                                    events=(pev, 2 * k, 2), events_per_phase=True)
         torch.cuda.synchronize()
         ms4 = sum(pev.elapsed_ms(2 * k, 2 * k + 1) for k in range(1, reps + 1)) / reps / (c4["W"] - 1)
         pev.close()
         b4 = 3 * n4 * c4["W"] * 2
-        roof["cache_free"] = {"workload": "cfg4_rs_ag_w8_bf16_2GiB_shard:reduce_scatter, in place",
+        roof["cache_free"] = {"workload": "cfg4_rs_ag_w8_bf16_2GiB_shard:reduce_scatter, in place, every step one pass over the whole "
+                                          "2 GiB blocks (opts.slab_bytes = -1)",
                               "kernel": "reduce_copy_vec<bf16,NSRC=2,NDST=1> (one wavefront x 1 vector per workgroup at this size)",
                               "bytes_per_launch": b4, "avg_launch_ms": round(ms4, 4),
                               "achieved": round(b4 / (ms4 * 1e-3) / 1e9, 1), "unit": "GB/s",
@@ -502,7 +530,7 @@ def main():
         "config": {"workload": name, "op": op, "W": W, "count_per_rank": count, "bytes_per_rank": S,
                    "chunk_bytes": chunk_bytes, "sched": args.sched, "xport": xport, "fuse_rs_ag": fuse,
                    "inplace": bool(args.inplace), "launches_per_step": launches, "graph_replay": bool(args.graph), "accumulate": args.accumulate,
-                   "reduce_op": args.reduce_op if reducing else None, "order": args.order, "chains": args.chains,
+                   "reduce_op": args.reduce_op if reducing else None, "order": args.order, "chains": args.chains, "slabs": n_slabs,
                    "layout": "separate allocations" if args.separate_allocations
                              else f"all buffers carved from one allocation, 256-byte aligned, {args.pad_bytes} bytes between them"},
         "algbw_rank_equiv_GBps": round(W * value, 2),

@@ -175,6 +175,13 @@ typedef struct hcl_opts {
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
   int accumulate;          /* hcl_acc_t; anything but PER_HOP needs sched == FUSED           */
   int order;               /* hcl_order_t; TREE needs sched == FUSED                          */
+  size_t slab_bytes;       /* STEPWISE, DIRECT: the ring runs to completion (all Reduce-Scatter steps, then
+                              all All-Gather steps) on one slab of every block before the next slab
+                              starts; a slab is as many whole chunks as keep what one step writes, all
+                              blocks together, within this many bytes.  0 = default: 256 MiB, the
+                              last-level cache, so that a step's incoming operand is still cached
+                              when the next launch reads it, at any message size; (size_t)-1 = no
+                              slabs, every step one pass over the whole blocks.  Same bits           */
   void *aux_stream;        /* STEPWISE only, optional: a second hipStream_t.  The chunks of every step
                               are split in two halves; the second half's launches go to this stream,
                               as a dependency chain of their own (chunk j of a step needs only chunk

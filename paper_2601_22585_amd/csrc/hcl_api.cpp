@@ -223,6 +223,8 @@ struct Ctx {
   void* stream2 = nullptr;    // second dependency chain (opts->aux_stream), STEPWISE only
   bool forked = false;        // stream2 currently waits on / runs ahead of `stream`
   int steps_issued = 0;       // step launches so far: odd ones walk their tiles backwards
+  uint64_t slab_lo = 0, slab_hi = ~0ull;  // launches cover these elements of every segment only (see for_each_slab)
+  uint64_t slab_budget = kLastLevelCache;  // bytes one step may write per slab; ~0 = no slabs
   bool chains_planned = false;
   uint64_t split_elems = 0;   // elements of a segment before this offset: caller's stream; from it on: stream2
 
@@ -259,6 +261,8 @@ struct Ctx {
     if (o && o->n_events < 0) return fail(HCL_ERR_INVALID_ARG, "n_events < 0");
     if (o && o->n_events > 0 && !o->events) return fail(HCL_ERR_INVALID_ARG, "n_events > 0 with null events");
     phase_events = o && o->events_per_phase;
+    if (o && o->slab_bytes) slab_budget = o->slab_bytes == (size_t)-1 ? ~0ull : (uint64_t)o->slab_bytes;
+    if (xport == HCL_XPORT_HOST_STAGED) slab_budget = ~0ull;  // bound by the host link, and the inbox slots hold whole blocks
     if (o && o->aux_stream) {
       if (sched != HCL_SCHED_STEPWISE) return fail(HCL_ERR_UNSUPPORTED, "aux_stream: the fused schedule is one launch, there is no chain to split");
       if (o->aux_stream == st) return fail(HCL_ERR_INVALID_ARG, "aux_stream must differ from the stream of the call");
@@ -297,6 +301,33 @@ struct Ctx {
     if (forced >= 0) return (uint32_t)forced;
     if (tiles_per_chunk > 17) return 17;
     return tiles_per_chunk > 1 ? 1 : 0;
+  }
+
+  // Slabs.  Chunk j of a step needs only chunk j of the step before, so the ring can run to
+  // completion -- every Reduce-Scatter step, then every All-Gather step -- on one slab of every
+  // block before it touches the next slab, which is also how the vendor libraries walk a large
+  // buffer.  A slab is as many whole chunks as keep one step's output (all blocks together)
+  // within the last-level cache: then every step's incoming operand is still there when the next
+  // launch reads it, at any message size.  body(first) issues the steps of one slab.
+  template <class F>
+  hcl_status_t for_each_slab(uint64_t block_elems, uint64_t blocks_per_step, F body) {
+    uint64_t slab = block_elems;
+    if (slab_budget != ~0ull) {
+      const uint64_t granule = chunk_elems ? chunk_elems : (uint64_t)(1u << 16);
+      const uint64_t fit = slab_budget / (blocks_per_step * es);
+      slab = fit / granule * granule;
+      if (slab == 0) slab = granule;
+      if (slab > block_elems) slab = block_elems;
+    }
+    hcl_status_t st = HCL_OK;
+    for (uint64_t lo = 0; lo < block_elems && !st; lo += slab) {
+      slab_lo = lo;
+      slab_hi = lo + slab;
+      st = body(lo == 0);
+    }
+    slab_lo = 0;
+    slab_hi = ~0ull;
+    return st;
   }
 
   // Default: one tile per workgroup, which measured faster on MI355X than a
@@ -371,8 +402,11 @@ struct Ctx {
     // are what the next one reads -- and one wavefront x 1 vector beyond that, where it measured
     // 2-5 % faster (W = 16 at 1 GiB per rank, 2 GiB blocks) and far less sensitive to where the
     // buffers lie in memory.
-    uint64_t step_bytes = 0;
-    for (uint32_t i = 0; i < a.nseg; ++i) step_bytes += a.seg[i].n * es;
+    uint64_t step_bytes = 0;  // what this step writes within the slab in progress
+    for (uint32_t i = 0; i < a.nseg; ++i) {
+      const uint64_t top = a.seg[i].n < slab_hi ? a.seg[i].n : slab_hi;
+      if (top > slab_lo) step_bytes += (top - slab_lo) * es;
+    }
     if (auto_threads && auto_unroll && (nsrc == 1 || step_bytes > kSmallTileFrom)) {
       t.threads = 64;
       t.unroll = 1;
@@ -383,11 +417,14 @@ struct Ctx {
     // per rank on MI355X); beyond, and for results no later launch reads, non-temporal stores are
     // 2-7 % faster.  Pinned host memory is always written with non-temporal stores.
     if (auto_nt) t.nt = (reread && xport == HCL_XPORT_DIRECT && step_bytes <= kLastLevelCache) ? 1 : 2;
-    if (split_elems == 0 || maxn <= split_elems) return launch_range(a, nsrc, ndst, t, 0, maxn, stream);
+    // the slab in progress, and within it the two chains' shares
+    const uint64_t lo = slab_lo, hi = maxn < slab_hi ? maxn : slab_hi;
+    if (lo >= hi) return HCL_OK;
+    if (split_elems == 0 || hi <= split_elems) return launch_range(a, nsrc, ndst, t, lo, hi, stream);
     hcl_status_t st = fork();
     if (st) return st;
-    if ((st = launch_range(a, nsrc, ndst, t, 0, split_elems, stream))) return st;
-    return launch_range(a, nsrc, ndst, t, split_elems, maxn, stream2);
+    if (lo < split_elems && (st = launch_range(a, nsrc, ndst, t, lo, split_elems, stream))) return st;
+    return launch_range(a, nsrc, ndst, t, lo > split_elems ? lo : split_elems, hi, stream2);
   }
 
   // Elements [lo, hi) of every segment of `a`, on stream `on`: as many launches as the tile
@@ -833,10 +870,14 @@ extern "C" hcl_status_t hcl_allreduce_sim(const void* const* send, void* const* 
     fin[r] = off(recv[r], bm.lo(r), c.es);
     push[r] = off(recv[c.ring.next(r)], bm.lo(r), c.es);
   }
-  if ((st = c.phase())) return st;
-  if ((st = run_rs(c, bm, send, part, send, fin, fuse ? push : nullptr, nullptr, 0, ib, /*forward_last=*/true, /*final_reread=*/true))) return st;
-  if ((st = c.phase())) return st;
-  if ((st = run_ag(c, bm, part, nullptr, fuse ? 1 : 0, ib, W - 1))) return st;
+  st = c.for_each_slab(bm.B, (uint64_t)W, [&](bool first) -> hcl_status_t {
+    hcl_status_t s2;
+    if (first && (s2 = c.phase())) return s2;
+    if ((s2 = run_rs(c, bm, send, part, send, fin, fuse ? push : nullptr, nullptr, 0, ib, /*forward_last=*/true, /*final_reread=*/true))) return s2;
+    if (first && (s2 = c.phase())) return s2;
+    return run_ag(c, bm, part, nullptr, fuse ? 1 : 0, ib, W - 1);
+  });
+  if (st) return st;
   return c.finish();
 }
 
@@ -892,7 +933,10 @@ extern "C" hcl_status_t hcl_reduce_scatter_sim(const void* const* send, void* co
     fin[r] = (char*)recv[r];
   }
   if ((st = c.phase())) return st;
-  if ((st = run_rs(c, bm, send, part, send, fin, nullptr, ws, ws_slot, ib, /*forward_last=*/false, /*final_reread=*/false))) return st;
+  st = c.for_each_slab(n, (uint64_t)W, [&](bool) -> hcl_status_t {
+    return run_rs(c, bm, send, part, send, fin, nullptr, ws, ws_slot, ib, /*forward_last=*/false, /*final_reread=*/false);
+  });
+  if (st) return st;
   return c.finish();
 }
 
@@ -928,24 +972,27 @@ extern "C" hcl_status_t hcl_all_gather_sim(const void* const* send, void* const*
   for (int r = 0; r < W; ++r) buf[r] = (char*)recv[r];
   const bool staged = c.xport == HCL_XPORT_HOST_STAGED;
   if ((st = c.phase())) return st;
-  if (staged && W > 1) {
-    // every rank puts its own block into its successor's inbox (and, out of
-    // place, into its own result)
-    StepArgs a{};
-    for (int k = 0; k < W; ++k) {
-      const int r = c.ring.order[k];
-      add_seg(a, send[r], nullptr, ib.slot(c.ring.next(r), 0), inplace ? nullptr : off(recv[r], bm.lo(r), es), n);
+  st = c.for_each_slab(n, (uint64_t)W, [&](bool) -> hcl_status_t {
+    hcl_status_t s2;
+    if (staged && W > 1) {
+      // every rank puts its own block into its successor's inbox (and, out of
+      // place, into its own result)
+      StepArgs a{};
+      for (int k = 0; k < W; ++k) {
+        const int r = c.ring.order[k];
+        add_seg(a, send[r], nullptr, ib.slot(c.ring.next(r), 0), inplace ? nullptr : off(recv[r], bm.lo(r), es), n);
+      }
+      if ((s2 = c.launch(a, 1, inplace ? 1 : 2, true))) return s2;
+    } else if (!inplace) {
+      // own block into own result
+      StepArgs a{};
+      for (int r = 0; r < W; ++r) add_seg(a, send[r], nullptr, off(recv[r], bm.lo(r), es), nullptr, n);
+      if ((s2 = c.launch(a, 1, 1, false))) return s2;
     }
-    if ((st = c.launch(a, 1, inplace ? 1 : 2, true))) return st;
-  } else if (!inplace) {
-    // own block into own result
-    StepArgs a{};
-    for (int r = 0; r < W; ++r) add_seg(a, send[r], nullptr, off(recv[r], bm.lo(r), es), nullptr, n);
-    if ((st = c.launch(a, 1, 1, false))) return st;
-  }
-  if (W > 1) {
-    if ((st = run_ag(c, bm, buf, (inplace || staged) ? nullptr : send, 0, ib, 0))) return st;
-  }
+    if (W > 1) return run_ag(c, bm, buf, (inplace || staged) ? nullptr : send, 0, ib, 0);
+    return HCL_OK;
+  });
+  if (st) return st;
   return c.finish();
 }
 
@@ -1011,15 +1058,20 @@ extern "C" hcl_status_t hcl_reduce_sim(const void* const* send, void* const* rec
   }
   // hop k (1 .. W-1): the k-th rank after the first sender adds its vector to what arrived
   const int p0 = c.ring.pos[root];
-  for (int k = 1; k <= W - 1; ++k) {
-    const int r = c.ring.at(p0 + 1 + k), p = c.ring.at(p0 + k);
-    // the travelling partial sum stays in the one workspace slot: read, combined, written back
-    const char* in = k == 1 ? (const char*)send[p] : ws;
-    char* out_p = k == W - 1 ? (char*)recv[root] : ws;
-    StepArgs a{};
-    add_seg(a, in, send[r], out_p, nullptr, count);
-    if ((st = c.launch(a, 2, 1, k < W - 1))) return st;
-  }
+  st = c.for_each_slab(count, 1, [&](bool) -> hcl_status_t {
+    for (int k = 1; k <= W - 1; ++k) {
+      const int r = c.ring.at(p0 + 1 + k), p = c.ring.at(p0 + k);
+      // the travelling partial sum stays in the one workspace slot: read, combined, written back
+      const char* in = k == 1 ? (const char*)send[p] : ws;
+      char* out_p = k == W - 1 ? (char*)recv[root] : ws;
+      StepArgs a{};
+      add_seg(a, in, send[r], out_p, nullptr, count);
+      hcl_status_t s2 = c.launch(a, 2, 1, k < W - 1);
+      if (s2) return s2;
+    }
+    return HCL_OK;
+  });
+  if (st) return st;
   return c.finish();
 }
 
@@ -1056,19 +1108,24 @@ extern "C" hcl_status_t hcl_broadcast_sim(const void* const* send, void* const* 
   // hop k: the k-th rank after the root copies what its predecessor holds; the
   // first launch also puts the root's vector into its own result when out of place
   const int p0 = c.ring.pos[root];
-  bool own_done = send[root] == recv[root];
-  for (int k = 1; k <= W - 1 || !own_done; ++k) {
-    StepArgs a{};
-    if (!own_done) {
-      add_seg(a, send[root], nullptr, recv[root], nullptr, count);
-      own_done = true;
+  st = c.for_each_slab(count, 1, [&](bool) -> hcl_status_t {
+    bool own_done = send[root] == recv[root];
+    for (int k = 1; k <= W - 1 || !own_done; ++k) {
+      StepArgs a{};
+      if (!own_done) {
+        add_seg(a, send[root], nullptr, recv[root], nullptr, count);
+        own_done = true;
+      }
+      if (k <= W - 1) {
+        const int r = c.ring.at(p0 + k), p = c.ring.at(p0 + k - 1);
+        add_seg(a, k == 1 ? send[root] : (const void*)recv[p], nullptr, recv[r], nullptr, count);
+      }
+      hcl_status_t s2 = c.launch(a, 1, 1, k < W - 1);
+      if (s2) return s2;
     }
-    if (k <= W - 1) {
-      const int r = c.ring.at(p0 + k), p = c.ring.at(p0 + k - 1);
-      add_seg(a, k == 1 ? send[root] : (const void*)recv[p], nullptr, recv[r], nullptr, count);
-    }
-    if ((st = c.launch(a, 1, 1, k < W - 1))) return st;
-  }
+    return HCL_OK;
+  });
+  if (st) return st;
   return c.finish();
 }
 

@@ -68,6 +68,7 @@ class Opts(ctypes.Structure):
         ("n_launches", ctypes.POINTER(ctypes.c_int)),
         ("accumulate", ctypes.c_int),
         ("order", ctypes.c_int),
+        ("slab_bytes", ctypes.c_size_t),
         ("aux_stream", ctypes.c_void_p),
         ("aux_events", ctypes.POINTER(ctypes.c_void_p)),
     ]
@@ -176,7 +177,7 @@ class EventList:
 
 def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, host_stage=None,
               threads=0, blocks=0, unroll=0, nontemporal=0, fuse_rs_ag=False, events=None,
-              events_per_phase=False, accumulate=0, order=0, aux_stream=None, aux_events=None):
+              events_per_phase=False, accumulate=0, order=0, aux_stream=None, aux_events=None, slab_bytes=0):
     """Builds the hcl_opts_t struct.  Returns (opts, keepalive): keep `keepalive`
     referenced until the call has returned."""
     o = Opts()
@@ -208,6 +209,7 @@ def make_opts(W, ring=None, sched="stepwise", xport="direct", workspace=None, ho
         o.n_events = n
         o.events_per_phase = 1 if events_per_phase else 0
         keep.append(ev)
+    o.slab_bytes = ctypes.c_size_t(-1).value if slab_bytes < 0 else int(slab_bytes)
     if aux_stream is not None:
         # a torch stream and an EventList of two events: the second dependency chain
         o.aux_stream = aux_stream.cuda_stream

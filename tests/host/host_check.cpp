@@ -213,6 +213,7 @@ struct Case {
   std::vector<int> ring;
   int threads, unroll, blocks;
   uint64_t misalign;
+  size_t slab_bytes;  // 0 default, (size_t)-1 none, else what one step may write per slab
 };
 
 static void fill_input(Mem& m, int b, int rank, int64_t idx0) {
@@ -251,6 +252,7 @@ static hcl_opts_t make_opts(const Case& c, Mem& m, int kind, void* const* events
   o.unroll = c.unroll;
   o.blocks = c.blocks;
   o.fuse_rs_ag = c.fuse_rs_ag;
+  o.slab_bytes = c.slab_bytes;
   if (c.two_chains) {
     o.aux_stream = AUX;
     o.aux_events = events;
@@ -298,9 +300,9 @@ static void check_stream_ops(const Case& c, size_t nlaunch) {
 
 static std::string describe(const char* kind, const Case& c) {
   char b[256];
-  snprintf(b, sizeof b, "%s W=%d n=%llu dtype=%d chunk=%llu inplace=%d fused=%d staged=%d fuse=%d chains=%d shape=%dx%d blocks=%d mis=%llu",
+  snprintf(b, sizeof b, "%s W=%d n=%llu dtype=%d chunk=%llu inplace=%d fused=%d staged=%d fuse=%d chains=%d shape=%dx%d blocks=%d mis=%llu slab=%lld",
            kind, c.W, (unsigned long long)c.n, c.dtype, (unsigned long long)c.chunk_elems, c.inplace, c.fused, c.staged,
-           c.fuse_rs_ag, c.two_chains ? 2 : 1, c.threads, c.unroll, c.blocks, (unsigned long long)c.misalign);
+           c.fuse_rs_ag, c.two_chains ? 2 : 1, c.threads, c.unroll, c.blocks, (unsigned long long)c.misalign, (long long)c.slab_bytes);
   return b;
 }
 
@@ -547,6 +549,7 @@ static void check_large(uint64_t n, int dtype, uint64_t chunk_bytes, int threads
   memset(&o, 0, sizeof o);
   o.threads = threads;
   o.unroll = unroll;
+  o.slab_bytes = (size_t)-1;  // every step one pass: consecutive launches that cover W blocks form a step
   void* ev[2] = {(void*)0x1, (void*)0x2};
   if (two_chains) {
     o.aux_stream = AUX;
@@ -598,6 +601,44 @@ static void check_large(uint64_t n, int dtype, uint64_t chunk_bytes, int threads
   if (steps != (size_t)W - 1 || covered) bad("%zu complete steps, expected %d", steps, W - 1);
 }
 
+// The default slab budget on the ZeRO-style shape: 2 GiB blocks in 64 slabs of 32 MiB, every
+// launch writing at most 256 MiB, all launches together every element once per step.
+static void check_large_slabs() {
+  g_case = "large reduce-scatter, default slabs";
+  const int W = 8;
+  const uint64_t n = (uint64_t)1 << 30, es = 2;
+  const uintptr_t base = 0x200000000000ull, stride = 0x4000000000ull;
+  const void* send[16];
+  void* recv[16];
+  for (int r = 0; r < W; ++r) {
+    send[r] = (void*)(base + (uintptr_t)r * stride);
+    recv[r] = (void*)(base + (uintptr_t)(W + r) * stride);
+  }
+  hcl_opts_t o;
+  memset(&o, 0, sizeof o);
+  o.workspace_bytes = hcl_workspace_bytes(HCL_KIND_REDUCE_SCATTER, W, n, HCL_BF16, 4 << 20, &o);
+  o.workspace = (void*)(base + (uintptr_t)(2 * W) * stride);
+  shim::reset();
+  hcl_status_t st = hcl_reduce_scatter_sim(send, recv, W, n, HCL_BF16, HCL_SUM, 4 << 20, &o, MAIN);
+  if (st != HCL_OK) { bad("status %s: %s", hcl_status_string(st), hcl_last_error()); return; }
+  const auto& L = shim::launches();
+  if (L.size() != 64u * (W - 1)) bad("%zu launches, expected 64 slabs x %d steps", L.size(), W - 1);
+  uint64_t total = 0;
+  for (size_t li = 0; li < L.size(); ++li) {
+    uint64_t wrote = 0;
+    for (uint32_t s2 = 0; s2 < L[li].step.nseg; ++s2) wrote += L[li].step.seg[s2].n;
+    if (wrote * es > (256ull << 20)) bad("launch %zu writes %llu bytes, more than the slab budget", li, (unsigned long long)(wrote * es));
+    total += wrote;
+    // launch li belongs to slab li / (W - 1): its segments start that many slabs into their blocks
+    const uint64_t slab = (uint64_t)(li / (W - 1)) * (32ull << 20);
+    const uintptr_t d = (uintptr_t)L[li].step.seg[0].dst0;
+    const uint64_t off = (d - base) % stride;
+    const bool last = li % (W - 1) == (size_t)(W - 2);
+    if (last ? off != slab : (off % ((2ull << 30) + 4096)) != slab) bad("launch %zu does not start at its slab", li);
+  }
+  if (total != (uint64_t)(W - 1) * W * n) bad("the launches write %llu elements in all, expected %llu", (unsigned long long)total, (unsigned long long)((W - 1) * W * n));
+}
+
 static void check_validation() {
   g_case = "validation";
   const void* send[16];
@@ -630,7 +671,7 @@ static void check_validation() {
 int main(int argc, char** argv) {
   if (argc > 1 && !strcmp(argv[1], "dump")) {
     setenv("HCL_DEBUG", "1", 1);
-    Case c{4, 10, HCL_FP32, 2, false, false, false, false, false, {2, 0, 3, 1}, 0, 0, 0, 0};
+    Case c{4, 10, HCL_FP32, 2, false, false, false, false, false, {2, 0, 3, 1}, 0, 0, 0, 0, 0};
     run_allreduce(c);
     return g_fail ? 1 : 0;
   }
@@ -659,6 +700,7 @@ int main(int argc, char** argv) {
       c.unroll = (int[]){0, 0, 1, 4}[rng() % 4];
       c.blocks = (int[]){0, 0, 3}[rng() % 3];
       c.misalign = rng() % 4 == 0 ? 1 : 0;
+      c.slab_bytes = (size_t[]){0, 0, (size_t)-1, 64, 200, 1024}[rng() % 6];  // small budgets: several slabs per block
       run_allreduce(c);
       run_rs_then_ag(c);
       Case d = c;
@@ -673,6 +715,7 @@ int main(int argc, char** argv) {
   check_large((uint64_t)1 << 29, HCL_UINT8, 1, 64, 1, false, 3);            // one tile per byte: 2^32 tiles a step
   check_large((uint64_t)1 << 29, HCL_UINT8, 1, 64, 1, true, 4);
   check_large(((uint64_t)1 << 30) + 12345, HCL_FP64, 0, 64, 1, false, 1);   // one chunk of 8 GiB per block
+  check_large_slabs();
   if (g_fail) {
     fprintf(stderr, "host_check: %d failure(s)\n", g_fail);
     return 1;

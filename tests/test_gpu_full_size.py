@@ -134,7 +134,8 @@ def test_config4_named_size_reduce_scatter_then_all_gather(cfg_id):
     # --- Reduce-Scatter, out of place: STEPWISE with workspace, then FUSED ---
     ws = torch.empty(hcl.workspace_bytes(hcl.KIND_REDUCE_SCATTER, W, n, code, chunk), dtype=torch.uint8, device="cuda")
     shard = [torch.zeros(n, dtype=wl.TORCH_DTYPE[dtype], device="cuda") for _ in range(W)]
-    assert hcl.reduce_scatter_sim(send, shard, chunk_bytes=chunk, workspace=ws) == W - 1
+    slabs = n * es * W // (256 << 20)               # a step's output is cut into slabs of 256 MiB
+    assert hcl.reduce_scatter_sim(send, shard, chunk_bytes=chunk, workspace=ws) == slabs * (W - 1)
     torch.cuda.synchronize()
     del ws
     check_shards(shard, "stepwise out of place")
@@ -161,6 +162,8 @@ def test_config4_named_size_reduce_scatter_then_all_gather(cfg_id):
     # --- Reduce-Scatter in place: STEPWISE, then (inputs drawn again) FUSED ---
     inpl = [send[r][r * n:(r + 1) * n] for r in range(W)]
     for sched in ("stepwise", "fused"):
+        # in place: once slab by slab (the default), and -- for the fused schedule's turn, which has no slabs --
+        # nothing to choose
         hcl.reduce_scatter_sim(send, inpl, chunk_bytes=chunk, sched=sched)
         torch.cuda.synchronize()
         check_shards(inpl, f"{sched} in place")
@@ -184,7 +187,7 @@ def test_config4_named_size_reduce_scatter_then_all_gather(cfg_id):
     for sched in ("stepwise", "fused"):
         for t in full:
             _view_int(t).fill_(0x55)
-        assert hcl.all_gather_sim(shard, full, chunk_bytes=chunk, sched=sched) == (W if sched == "stepwise" else 1)
+        assert hcl.all_gather_sim(shard, full, chunk_bytes=chunk, sched=sched) == (slabs * W if sched == "stepwise" else 1)
         torch.cuda.synchronize()
         check_full(f"all-gather {sched}")
     for t in full:
@@ -192,9 +195,17 @@ def test_config4_named_size_reduce_scatter_then_all_gather(cfg_id):
     own = [full[r][r * n:(r + 1) * n] for r in range(W)]
     for r in range(W):
         own[r].copy_(shard[r])
-    assert hcl.all_gather_sim(own, full, chunk_bytes=chunk) == W - 1
+    assert hcl.all_gather_sim(own, full, chunk_bytes=chunk) == slabs * (W - 1)
     torch.cuda.synchronize()
     check_full("all-gather stepwise in place")
+    # and once more as single passes over the whole 2 GiB blocks (no slabs)
+    for t in full:
+        _view_int(t).fill_(0x44)
+    for r in range(W):
+        own[r].copy_(shard[r])
+    assert hcl.all_gather_sim(own, full, chunk_bytes=chunk, slab_bytes=-1) == W - 1
+    torch.cuda.synchronize()
+    check_full("all-gather stepwise in place, no slabs")
 
 
 def test_config5_named_size_host_staged_every_element():

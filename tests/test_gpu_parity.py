@@ -281,3 +281,26 @@ def test_two_dependency_chains_under_graph_capture():
             assert_same_bits(recv[r], want[r], dtype, f"two chains, graph replay {rep} rank {r}")
     del g
     ev.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_slabs_do_not_change_the_bits(dtype):
+    """opts.slab_bytes: the ring runs to completion on one slab of every block before the next.
+    Budgets that give 1, 2, 7 and many slabs, ragged blocks, both chains, in and out of place."""
+    es = wl.ESIZE[dtype]
+    for k, (W, count, chunk, slab) in enumerate([(8, 1_000_003, 16 * 1024, 8 * 64 * 1024), (4, 300_000, 4096, 4 * 4096),
+                                                 (5, 262_147, 0, 5 * es * 70_000), (16, 2_000_003, 64 * 1024, 1 << 20),
+                                                 (3, 100_000, es * 1000, -1)]):
+        for inplace in (False, True):
+            run_allreduce(850 + k, W, count, dtype, DIST[dtype], chunk_bytes=chunk, inplace=inplace, slab_bytes=slab)
+            run_allreduce(860 + k, W, count, dtype, DIST[dtype], chunk_bytes=chunk, inplace=inplace, slab_bytes=slab, fuse_rs_ag=True)
+    s2, ev = torch.cuda.Stream(), hcl.EventList(2)
+    n = run_allreduce(870, 8, 1_000_003, dtype, DIST[dtype], chunk_bytes=16 * 1024, slab_bytes=8 * 32 * 1024)
+    B = -(-1_000_003 // 8)
+    slabs = -(-B * es // (32 * 1024))
+    assert n == 14 * slabs
+    run_allreduce(871, 8, 1_000_003, dtype, DIST[dtype], chunk_bytes=16 * 1024, slab_bytes=8 * 64 * 1024, aux_stream=s2, aux_events=ev)
+    for inplace in (False, True):
+        run_reduce_scatter(872, 8, 125_003, dtype, DIST[dtype], chunk_bytes=8192, inplace=inplace, slab_bytes=8 * 16384)
+        run_all_gather(873, 8, 125_003, dtype, DIST[dtype], chunk_bytes=8192, inplace=inplace, slab_bytes=8 * 16384)
+    ev.close()

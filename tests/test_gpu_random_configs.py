@@ -50,6 +50,8 @@ def _case(rnd):
     c["xport"] = "host_staged" if (sched == "stepwise" and c["kind"] != "reduce" and rnd.random() < 0.3) else "direct"
     # the chunk range split over two streams, each half a dependency chain of its own
     c["two_chains"] = sched == "stepwise" and rnd.random() < 0.35
+    # slabs: what one step may write before the ring moves on to the next slab of every block
+    c["slab"] = rnd.choice([0, 0, -1, 4096, 65536, 1 << 20])
     n = rnd.choice([1, 17, 1000, 4096, 65_536, rnd.randrange(1, 200_000)])
     c["n"] = n
     chunk_elems = rnd.choice([0, 0, 1, 16, 1024, 8192, rnd.randrange(1, 50_000)])
@@ -66,7 +68,7 @@ def _run(c, seed):
                rounding=orc.ROUND_ONCE if c["acc"] == "fp32" else orc.ROUND_EACH)
     opt = dict(chunk_bytes=c["chunk"], ring=c["ring"], sched=c["sched"], op=c["op"], order=c["order"],
                accumulate=c["acc"], threads=c["threads"], unroll=c["unroll"], blocks=c["blocks"],
-               nontemporal=c["nontemporal"], xport=c["xport"])
+               nontemporal=c["nontemporal"], xport=c["xport"], slab_bytes=c["slab"])
     tag = f"seed {seed}: {c}"
     if c["two_chains"]:
         opt["aux_stream"], opt["aux_events"] = _second_chain()
