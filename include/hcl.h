@@ -166,12 +166,16 @@ typedef struct hcl_opts {
                               first All-Gather step is dropped (same bits, one read fewer)   */
   void *const *events;     /* measurement hook: host array of n_events hipEvent_t; event k is
                               recorded on the stream before launch k, and one more after the
-                              last launch; launches beyond n_events-1 are not bracketed     */
+                              last launch; launches beyond n_events-1 are not bracketed; all
+                              events are recorded on `stream`, also for launches that go to
+                              aux_stream                                                     */
   int n_events;
   int events_per_phase;    /* 0: as above.  1: events only at phase boundaries -- event 0 before the
                               first Reduce-Scatter launch (or the only phase of the call), event 1
                               before the first All-Gather launch of an All-Reduce, the next one
-                              after the last launch: the cheap way to time a phase's launches   */
+                              after the last launch: the cheap way to time a phase's launches
+                              (with several slabs, see slab_bytes, the two phases of an All-Reduce
+                              interleave and only the first and the last event are meaningful)  */
   int *n_launches;         /* if non-NULL, receives the number of kernel launches enqueued  */
   int accumulate;          /* hcl_acc_t; anything but PER_HOP needs sched == FUSED           */
   int order;               /* hcl_order_t; TREE needs sched == FUSED                          */
