@@ -67,7 +67,7 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
-EXAMPLES = ["allreduce_latency", "allreduce_from_file"]
+EXAMPLES = ["allreduce_latency", "allreduce_from_file", "allreduce_bandwidth"]
 
 
 def build_examples(verbose=False):

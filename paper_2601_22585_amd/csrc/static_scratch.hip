@@ -10,11 +10,11 @@
 #include "internal.h"
 #include "ring_sched.h"
 
-namespace {
-
 // Every GPU the process uses holds its own copy of this array, at its own
 // address, from the moment the code object is loaded there until the process ends.
-__device__ __align__(256) unsigned char scratch[HCL_STATIC_SCRATCH_BYTES];
+static __device__ __align__(256) unsigned char scratch[HCL_STATIC_SCRATCH_BYTES];
+
+namespace {
 
 constexpr int kMaxDevices = 64;
 void* g_scratch_of_device[kMaxDevices];  // device address of `scratch` on each device, once looked up
