@@ -67,24 +67,32 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
-EXAMPLES = ["allreduce_latency", "allreduce_from_file", "allreduce_bandwidth"]
+EXAMPLES = ["allreduce_latency", "allreduce_from_file", "allreduce_bandwidth"]   # plain C against the library
+PROBES = ["stream_ceilings"]   # stand-alone HIP programs that use no part of the library
 
 
 def build_examples(verbose=False):
-    """Compile the plain-C examples against the built library (they link libhcl.so by path).
-    Returns the executables' paths."""
+    """Compile the plain-C examples against the built library (they link libhcl.so by path)
+    and the stand-alone HIP probes.  Returns the executables' paths."""
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    exes = []
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    exes, cmds = [], []
     for name in EXAMPLES:
         src = os.path.join(HERE, "examples", name + ".c")
         exe = os.path.join(HERE, "examples", name)
-        cmd = ["gcc", "-O2", "-std=gnu11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
-               "-I", os.path.join(ROOT, "include"), src, "-L", HERE, "-lhcl", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
-               "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe]
+        cmds.append(["gcc", "-O2", "-std=gnu11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+                     "-I", os.path.join(ROOT, "include"), src, "-L", HERE, "-lhcl", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+                     "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe])
+        exes.append(exe)
+    for name in PROBES:
+        exe = os.path.join(HERE, "examples", name)
+        cmds.append([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                     "-Wno-unknown-warning-option", os.path.join(HERE, "examples", name + ".hip"), "-o", exe])
+        exes.append(exe)
+    for cmd in cmds:
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
-        exes.append(exe)
     return exes
 
 

@@ -199,6 +199,9 @@ int env_int(const char* name, int dflt) {
 constexpr uint64_t kSmallTileFrom = 512ull << 20;
 // capacity of the memory-side last-level cache (MI355X: 256 MiB)
 constexpr uint64_t kLastLevelCache = 256ull << 20;
+// how much of one block the one-source fused kernel walks before it moves to the next, for blocks of
+// kGatherBigBlock bytes and more
+constexpr uint64_t kGatherBigChunk = 64ull << 20;
 
 struct Ctx {
   Ring ring;
@@ -332,8 +335,12 @@ struct Ctx {
 
   // Default: one tile per workgroup, which measured faster on MI355X than a
   // persistent grid; opts->blocks caps the grid and the kernels then stride.
-  int grid_for(uint32_t total_tiles) const {
-    const uint32_t cap = max_blocks ? (uint32_t)max_blocks : 0x7FFFFFFFu;
+  // The runtime refuses a launch of 2^32 threads or more, so a larger one
+  // strides as well.
+  int grid_for(uint32_t total_tiles, int threads) const {
+    uint32_t cap = 0xFFFFFFFFu / (uint32_t)(threads > 0 ? threads : 1);
+    if (cap > 0x7FFFFFFFu) cap = 0x7FFFFFFFu;
+    if (max_blocks && (uint32_t)max_blocks < cap) cap = (uint32_t)max_blocks;
     return (int)(total_tiles < cap ? total_tiles : cap);
   }
 
@@ -484,7 +491,7 @@ struct Ctx {
       if (b.nseg == 0) return HCL_OK;
     }
     b.total_tiles = (uint32_t)((c1 - c0) * b.nseg * b.tiles_per_chunk);
-    t.blocks = grid_for(b.total_tiles);
+    t.blocks = grid_for(b.total_tiles, t.threads);
     hcl_status_t st = mark(launches);
     if (st) return st;
     int rc = launch_step(b, dtype, nsrc, ndst, t, on);
@@ -498,6 +505,9 @@ struct Ctx {
     const bool one_block = a.mode >= 3;  // Reduce / Broadcast
     const bool copy_mode = a.mode == 2 || a.mode == 4;
     uint64_t chunk = (chunk_elems && chunk_elems < a.B) ? chunk_elems : a.B;
+    // The chunk only orders the tiles.  The one-source kernel on blocks of 1 GiB and more measured
+    // 3 % faster on MI355X when it walks 64 MiB of a block before it moves to the next block.
+    if (copy_mode && a.B * es >= kGatherBigBlock && chunk * es < kGatherBigChunk) chunk = kGatherBigChunk / es;
     const uint64_t nchunks = ceil_div(a.B, chunk);
     Tuning t = tune;
     // the general-form kernel (operator other than the sum, or tree order) is
@@ -521,7 +531,7 @@ struct Ctx {
     a.op = copy_mode ? 0 : (uint8_t)op;
     a.tree = !copy_mode && tree;
     a.wide = !copy_mode && wide;
-    t.blocks = grid_for(a.total_tiles);
+    t.blocks = grid_for(a.total_tiles, t.threads);
     hcl_status_t st = mark(launches);
     if (st) return st;
     int rc = launch_fused(a, dtype, t, stream);

@@ -584,6 +584,9 @@ static void check_large(uint64_t n, int dtype, uint64_t chunk_bytes, int threads
     for (uint32_t s = 0; s < a.nseg; ++s) maxn = std::max(maxn, a.seg[s].n);
     const uint64_t want = ceil_div(maxn, a.chunk) * a.nseg * a.tiles_per_chunk;
     if (want > 0x7FFFFFFFull || a.total_tiles != want || a.tiles_per_chunk != ceil_div(a.chunk, tile)) bad("launch %zu: tile grid inconsistent or beyond 2^31 - 1 (%llu)", li, (unsigned long long)want);
+    // the runtime refuses a launch of 2^32 threads or more: larger tile counts must stride
+    const uint64_t grid = (uint64_t)L[li].tune.blocks, thr = (uint64_t)L[li].tune.threads;
+    if (grid < 1 || grid > a.total_tiles || grid * thr > 0xFFFFFFFFull) bad("launch %zu: grid %llu x %llu threads", li, (unsigned long long)grid, (unsigned long long)thr);
     for (uint32_t s = 0; s < a.nseg; ++s) {
       const uintptr_t lo = (uintptr_t)a.seg[s].dst0, hi = lo + a.seg[s].n * es;
       iv.push_back({lo, hi});
