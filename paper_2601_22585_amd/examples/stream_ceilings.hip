@@ -7,14 +7,19 @@
 // of the library is used: this is the yardstick, not the product.
 //
 //   stream_ceilings [total GiB moved per launch = 8] [launches timed = 5]
+//   stream_ceilings host [MiB per stream = 512] [launches timed = 3]
 //
 // Prints, per pattern, the best of a few launch shapes in GB/s and as a share
-// of 8 TB/s.
+// of 8 TB/s.  The `host` form puts streams in pinned host memory instead and
+// prints what kernels reach over the host link: reading it, writing it, and
+// both at once (the access pattern of a ring step whose blocks travel through
+// host memory: incoming block read from the host, outgoing block written to it).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { \
@@ -103,7 +108,57 @@ static void pattern(char* arena, size_t total_bytes, int reps) {
   fflush(stdout);
 }
 
+// Streams in pinned host memory: GB/s each way over the host link.
+template <int R, int D>
+static void host_pattern(const char* what, const Streams& s, size_t stream_bytes, int reps, int host_reads, int host_writes) {
+  const struct { int threads, unroll; } shapes[] = {{64, 1}, {128, 1}, {256, 1}, {64, 2}, {128, 2}, {64, 4}};
+  double best = 0.0;
+  int best_shape = 0;
+  for (int i = 0; i < 6; ++i) {
+    const int t = shapes[i].threads, u = shapes[i].unroll;
+    const double g = u == 1 ? time_shape<R, D, 1>(s, stream_bytes, t, reps)
+                   : u == 2 ? time_shape<R, D, 2>(s, stream_bytes, t, reps) : time_shape<R, D, 4>(s, stream_bytes, t, reps);
+    if (g > best) { best = g; best_shape = i; }
+  }
+  const double per_stream = best / (R + D);   // every stream moves stream_bytes in the same time
+  printf("%-44s host to device %5.1f GB/s, device to host %5.1f GB/s (%d threads x %d vectors)\n", what,
+         per_stream * host_reads, per_stream * host_writes, shapes[best_shape].threads, shapes[best_shape].unroll);
+  fflush(stdout);
+}
+
+static int host_link(size_t stream_bytes, int reps) {
+  char *h0, *h1, *dev;
+  CK(hipHostMalloc((void**)&h0, stream_bytes, hipHostMallocDefault));
+  CK(hipHostMalloc((void**)&h1, stream_bytes, hipHostMallocDefault));
+  CK(hipMalloc(&dev, 2 * stream_bytes));
+  fill_random<<<8192, 256>>>((uint32_t*)dev, 2 * stream_bytes / 4);
+  CK(hipDeviceSynchronize());
+  CK(hipMemcpy(h0, dev, stream_bytes, hipMemcpyDeviceToHost));
+  Streams s = {};
+  s.src[0] = (const u32x4*)h0; s.dst[0] = (u32x4*)dev;
+  host_pattern<1, 1>("read from host, write to device:", s, stream_bytes, reps, 1, 0);
+  s.src[0] = (const u32x4*)dev; s.dst[0] = (u32x4*)h1;
+  host_pattern<1, 1>("read from device, write to host:", s, stream_bytes, reps, 0, 1);
+  // both ways at once: sum of a host stream and a device stream, written to the device and to the host
+  s.src[0] = (const u32x4*)h0; s.src[1] = (const u32x4*)dev;
+  s.dst[0] = (u32x4*)(dev + stream_bytes); s.dst[1] = (u32x4*)h1;
+  host_pattern<2, 2>("read host + device, write device + host:", s, stream_bytes, reps, 1, 1);
+  CK(hipFree(dev));
+  CK(hipHostFree(h0));
+  CK(hipHostFree(h1));
+  return 0;
+}
+
 int main(int argc, char** argv) {
+  if (argc > 1 && !strcmp(argv[1], "host")) {
+    const size_t mib = argc > 2 ? (size_t)atol(argv[2]) : 512;
+    const int reps = argc > 3 ? atoi(argv[3]) : 3;
+    if (mib < 1 || mib > 8192 || reps < 1 || reps > 100) {
+      fprintf(stderr, "usage: %s host [MiB per stream 1..8192] [launches timed 1..100]\n", argv[0]);
+      return 2;
+    }
+    return host_link(mib << 20, reps);
+  }
   const size_t total = (size_t)(argc > 1 ? atol(argv[1]) : 8) << 30;
   const int reps = argc > 2 ? atoi(argv[2]) : 5;
   if (total < ((size_t)1 << 30) || total > ((size_t)64 << 30) || reps < 1 || reps > 1000) {
