@@ -49,7 +49,8 @@
  *     (64 KiB + 256 B, say) measured 3-7 % slower on MI355X.
  *   - Launch-shape fields of hcl_opts_t that are 0 may be overridden by the
  *     environment variables HCL_THREADS, HCL_UNROLL, HCL_BLOCKS,
- *     HCL_NONTEMPORAL and HCL_STAGGER (for sweeps); values in the struct win.
+ *     HCL_NONTEMPORAL, HCL_STAGGER and HCL_ZIGZAG (0 = every step walks its
+ *     tiles forwards) (for sweeps); values in the struct win.
  *   - HCL_DEBUG=1 in the environment makes every collective call print its
  *     arguments and the work items of its schedule (hcl_schedule_items) to
  *     stderr before it enqueues anything.
@@ -157,10 +158,12 @@ typedef struct hcl_opts {
                               and more), else 1, 2, 4 or 8 (8: step kernels only).  The FUSED
                               reductions always keep one vector per thread and rank           */
   int nontemporal;         /* cache policy of the memory accesses.  0 = default: non-temporal
-                              (streaming) loads; STEPWISE stores are regular while one step's
-                              output fits the 256 MiB last-level cache (the next step reads it) and
-                              non-temporal beyond; FUSED stores are non-temporal.  1 = loads and
-                              stores non-temporal, 2 = loads only, -1 = neither                  */
+                              (streaming) loads; a STEPWISE step whose output a later launch of
+                              the call reads, and which fits the 256 MiB last-level cache, writes
+                              it through the L2 so that the next launch finds it in that cache;
+                              all other stores are non-temporal.  1 = loads and stores
+                              non-temporal, 2 = loads non-temporal and step stores written
+                              through (FUSED: ordinary stores), -1 = ordinary loads and stores */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the
                               first All-Gather step is dropped (same bits, one read fewer)   */

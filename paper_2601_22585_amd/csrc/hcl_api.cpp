@@ -289,7 +289,7 @@ struct Ctx {
     tune.threads = threads;
     tune.unroll = unroll;
     auto_nt = nt == 0;
-    tune.nt = nt < 0 ? 0 : (nt == 2 ? 1 : 2);  // -1 off; 1 loads and stores; 2 loads only; 0: by size, see launch()
+    tune.nt = nt < 0 ? 0 : (nt == 2 ? 1 : 2);  // -1 off; 1 loads and stores; 2 loads, stores written through; 0: by size, see launch()
     max_blocks = blocks;  // 0 = decide at launch from the CU count
     return HCL_OK;
   }
@@ -401,29 +401,30 @@ struct Ctx {
     // Consecutive steps walk their tiles in opposite directions: the end of what one step wrote is
     // what the last-level cache still holds when the next step starts (+1.5 % at 256 MiB per rank,
     // where one step's output is as large as that cache; neutral elsewhere).
-    a.reverse = (uint32_t)(steps_issued++ & 1);
+    a.reverse = (uint32_t)(steps_issued++ & 1) & (uint32_t)(env_int("HCL_ZIGZAG", 1) != 0);  // the variable: for sweeps
     Tuning t = tune;
-    // Defaults from sweeps on MI355X.  Copying steps: one wavefront x 1 vector per workgroup.
-    // Reducing steps: 128 threads x 2 vectors per source while one step's output (all ranks
-    // together) is at most twice the 256 MiB last-level cache -- the partial sums one step writes
-    // are what the next one reads -- and one wavefront x 1 vector beyond that, where it measured
-    // 2-5 % faster (W = 16 at 1 GiB per rank, 2 GiB blocks) and far less sensitive to where the
-    // buffers lie in memory.
     uint64_t step_bytes = 0;  // what this step writes within the slab in progress
     for (uint32_t i = 0; i < a.nseg; ++i) {
       const uint64_t top = a.seg[i].n < slab_hi ? a.seg[i].n : slab_hi;
       if (top > slab_lo) step_bytes += (top - slab_lo) * es;
     }
-    if (auto_threads && auto_unroll && (nsrc == 1 || step_bytes > kSmallTileFrom)) {
+    // Cache policy.  Loads are non-temporal.  What a step writes is the incoming operand of the
+    // next step: while one step's output (all ranks together) fits the 256 MiB last-level cache,
+    // it is written through the L2 and the next launch finds it in that cache (on MI355X +7 to +8 %
+    // of HBM peak over non-temporal stores at 64 MiB to 1 GiB per rank, +4 to +5 over ordinary
+    // stores, whose dirty lines wait in the L2 for the end of the kernel); beyond, and for results
+    // no later launch reads, non-temporal stores.  Pinned host memory is always written with
+    // non-temporal stores.
+    if (auto_nt) t.nt = (reread && xport == HCL_XPORT_DIRECT && step_bytes <= kLastLevelCache) ? 1 : 2;
+    // Launch shape, from sweeps on MI355X: 128 threads x 2 vectors per source for steps that write
+    // through (reducing or copying); one wavefront x 1 vector for copies with non-temporal stores
+    // (84 % against 70 % of HBM peak) and for reducing steps that write more than 512 MiB, where it
+    // measured 2-5 % faster (W = 16 at 1 GiB per rank, 2 GiB blocks as one slab) and far less
+    // sensitive to where the buffers lie in memory.
+    if (auto_threads && auto_unroll && ((nsrc == 1 && t.nt != 1) || step_bytes > kSmallTileFrom)) {
       t.threads = 64;
       t.unroll = 1;
     }
-    // Cache policy.  Loads are non-temporal.  What a step writes is the incoming operand of the
-    // next step: while one step's output (all ranks together) fits the 256 MiB last-level cache,
-    // regular stores leave it there for the next launch (+2 to +4 % of bandwidth from 16 to 128 MiB
-    // per rank on MI355X); beyond, and for results no later launch reads, non-temporal stores are
-    // 2-7 % faster.  Pinned host memory is always written with non-temporal stores.
-    if (auto_nt) t.nt = (reread && xport == HCL_XPORT_DIRECT && step_bytes <= kLastLevelCache) ? 1 : 2;
     // the slab in progress, and within it the two chains' shares
     const uint64_t lo = slab_lo, hi = maxn < slab_hi ? maxn : slab_hi;
     if (lo >= hi) return HCL_OK;

@@ -57,8 +57,9 @@ struct Tuning {
   int threads;      // per workgroup, multiple of 64
   int blocks;       // workgroups
   int unroll;       // 1, 2, 4, 8
-  int nt;           // cache policy: 0 regular loads and stores; 1 non-temporal (streaming) loads, regular
-                    // stores; 2 non-temporal loads and stores.  The fused kernels know on (!= 0) and off
+  int nt;           // cache policy: 0 ordinary loads and stores; 1 non-temporal (streaming) loads, stores
+                    // written through the L2; 2 non-temporal loads and stores.  The fused kernels know
+                    // on (!= 0) and off
 };
 
 // Elements one tile covers for this dtype / tuning.

@@ -4,8 +4,8 @@
 // bytes moved), so the design targets HBM bandwidth, not the matrix cores: every
 // lane moves 128-bit vectors, a wavefront's 64 lanes cover 1 KiB of contiguous
 // memory per access, each thread issues all loads of a tile (UNROLL vectors
-// per source) before the first use, and streamed outputs use non-temporal
-// stores.  A launch covers one tile per workgroup, or strides over the tiles
+// per source) before the first use; outputs the next launch reads are written
+// through the L2, all others with non-temporal stores.  A launch covers one tile per workgroup, or strides over the tiles
 // when the grid is capped.
 #include "wire.h"
 #include "ring_sched.h"
@@ -16,12 +16,14 @@ namespace hcl {
 // STEPWISE: one ring step of every rank.  128-bit path.
 // ---------------------------------------------------------------------------
 // GEN: the operator is a.op at run time (product, maximum, minimum); otherwise the sum.
-// NT: 0 regular loads and stores; 1 non-temporal loads, regular stores -- what a step writes stays
-// in the 256 MiB last-level cache for the next step, which reads it as its incoming operand;
-// 2 non-temporal loads and stores, for outputs that exceed that cache anyway.
+// NT: 0 ordinary loads and stores; 1 non-temporal loads, stores written through the L2 -- what a
+// step writes is then in the 256 MiB last-level cache when the next step reads it as its incoming
+// operand; 2 non-temporal loads and stores, for outputs that exceed that cache or that no later
+// launch reads.
 template <int DT, int NSRC, int NDST, int UNROLL, int NT, bool GEN>
 __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
-  constexpr bool NTL = NT >= 1, NTS = NT == 2;
+  constexpr bool NTL = NT >= 1;
+  constexpr int NTS = NT == 2 ? ST_STREAM : NT == 1 ? ST_THROUGH : ST_PLAIN;
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
   constexpr uint32_t VE = 16 / ES;

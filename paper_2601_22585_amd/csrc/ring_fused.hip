@@ -71,9 +71,9 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
         }
         if (to_all) {
 #pragma unroll
-          for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
+          for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
         } else {
-          st16<NT>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+          st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + p.lo * ES + vi * 16u, acc);
         }
       }
     }
@@ -126,7 +126,7 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t vi = u * nthr + tid;
-        if (vi < nvec) st16<NT>(d + vi * 16u, v[u]);
+        if (vi < nvec) st16<NT ? ST_STREAM : ST_PLAIN>(d + vi * 16u, v[u]);
       }
     }
     const uint32_t e = nvec * VE + tid;
@@ -309,9 +309,9 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
         const u32x4 acc = combine_vec<DT, W>(v, op, tree, wide);
         if (to_all) {
 #pragma unroll
-          for (int r = 0; r < W; ++r) st16<NT>(a.dst[r] + voff + vi * 16u, acc);
+          for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
         } else {
-          st16<NT>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+          st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + p.lo * ES + vi * 16u, acc);
         }
       }
     }
