@@ -126,6 +126,17 @@ def test_launch_shapes_do_not_change_the_bits():
             run_allreduce(500, W, count, dtype, DIST[dtype], chunk_bytes=32 * 1024, sched=sched, **kw)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "int32"])
+def test_written_through_stores_in_strided_unrolled_launches(dtype):
+    """The stores that hand a step's output to the next launch are spelled out as an instruction
+    (wire.h) and carry their own wait states; a capped grid with several vectors per thread is where
+    a register that still holds store data is reused soonest."""
+    for kw in [dict(threads=256, unroll=4, blocks=64), dict(threads=64, unroll=8, blocks=301), dict(threads=128, unroll=2, blocks=1000)]:
+        run_allreduce(510, 8, 1_200_011, dtype, DIST[dtype], chunk_bytes=256 * 1024, nontemporal=2, **kw)
+        run_reduce_scatter(511, 4, 300_007, dtype, DIST[dtype], nontemporal=2, **kw)
+        run_all_gather(512, 4, 300_007, dtype, DIST[dtype], nontemporal=2, **kw)
+
+
 def _special_inputs(dtype, W, count):
     """Rank buffers salted with infinities, NaN, signed zeros, subnormals and near-overflow values."""
     g = torch.Generator().manual_seed(77)
