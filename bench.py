@@ -426,7 +426,13 @@ def main():
         one_block = op in ("reduce", "broadcast")
         gran = chunk_bytes // es if chunk_bytes else 65536
         slab = max(gran, budget // ((1 if one_block else W) * es) // gran * gran)
-        n_slabs = max(1, -(-(count if one_block else B) // slab))
+        blk, lo, n_slabs = (count if one_block else B), 0, 0
+        while lo < blk:   # the library's rule: a remainder of less than 1/32 of a slab joins the last slab
+            hi = lo + slab
+            if hi >= blk or blk - hi <= slab // 32:
+                hi = blk
+            n_slabs, lo = n_slabs + 1, hi
+        n_slabs = max(1, n_slabs)
     bytes_per_launch /= n_slabs
     units *= n_slabs
     n_dom *= n_slabs

@@ -185,7 +185,8 @@ typedef struct hcl_opts {
   size_t slab_bytes;       /* STEPWISE, DIRECT: the ring runs to completion (all Reduce-Scatter steps, then
                               all All-Gather steps) on one slab of every block before the next slab
                               starts; a slab is as many whole chunks as keep what one step writes, all
-                              blocks together, within this many bytes.  0 = default: 256 MiB, the
+                              blocks together, within this many bytes (a remainder of less than 1/32 of a
+                              slab joins the last one).  0 = default: 256 MiB, the
                               last-level cache, so that a step's incoming operand is still cached
                               when the next launch reads it, at any message size; (size_t)-1 = no
                               slabs, every step one pass over the whole blocks.  Same bits           */

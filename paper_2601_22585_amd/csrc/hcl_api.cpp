@@ -203,6 +203,20 @@ constexpr uint64_t kLastLevelCache = 256ull << 20;
 // kGatherBigBlock bytes and more
 constexpr uint64_t kGatherBigChunk = 64ull << 20;
 
+// The chunk a launch orders its tiles by: about `chunk` elements, but such that n elements make a
+// whole number of equal chunks of whole tiles.  A block of 8 chunks and one element would otherwise
+// get a ninth row of tiles with one element of work in it (a tenth of the workgroups of every
+// launch empty: 4 % of bandwidth on MI355X), and a chunk that is no multiple of the tile would end
+// in a partial tile.
+uint64_t even_chunk(uint64_t n, uint64_t chunk, uint64_t tile) {
+  if (n == 0 || chunk == 0) return chunk;
+  uint64_t k = (n + chunk / 2) / chunk;
+  if (k == 0) k = 1;
+  uint64_t even = round_up(ceil_div(n, k), tile);
+  if (even > (tile << 20)) even = round_up(ceil_div(n, k + 1), tile);
+  return even;
+}
+
 struct Ctx {
   Ring ring;
   int W = 0;
@@ -323,10 +337,15 @@ struct Ctx {
       if (slab > block_elems) slab = block_elems;
     }
     hcl_status_t st = HCL_OK;
-    for (uint64_t lo = 0; lo < block_elems && !st; lo += slab) {
+    for (uint64_t lo = 0; lo < block_elems && !st;) {
+      // a remainder of less than 1/32 of a slab joins the last slab: a ring of its own over a few
+      // elements would cost 2 (W - 1) launches for nothing (blocks of 8 chunks and 64 elements: 4 %)
+      uint64_t hi = lo + slab;
+      if (hi >= block_elems || block_elems - hi <= slab / 32) hi = block_elems;
       slab_lo = lo;
-      slab_hi = lo + slab;
+      slab_hi = hi;
       st = body(lo == 0);
+      lo = hi;
     }
     slab_lo = 0;
     slab_hi = ~0ull;
@@ -415,7 +434,8 @@ struct Ctx {
     // stores, whose dirty lines wait in the L2 for the end of the kernel); beyond, and for results
     // no later launch reads, non-temporal stores.  Pinned host memory is always written with
     // non-temporal stores.
-    if (auto_nt) t.nt = (reread && xport == HCL_XPORT_DIRECT && step_bytes <= kLastLevelCache) ? 1 : 2;
+    // (a slab may exceed the budget by 1/32, see for_each_slab)
+    if (auto_nt) t.nt = (reread && xport == HCL_XPORT_DIRECT && step_bytes <= kLastLevelCache + kLastLevelCache / 32) ? 1 : 2;
     // Launch shape, from sweeps on MI355X: 128 threads x 2 vectors per source for steps that write
     // through (reducing or copying); one wavefront x 1 vector for copies with non-temporal stores
     // (84 % against 70 % of HBM peak) and for reducing steps that write more than 512 MiB, where it
@@ -458,6 +478,7 @@ struct Ctx {
     // a chunk only orders the work: a longer one is walked in pieces of 2^20 tiles, so that any
     // number of chunks can be split over launches of at most 2^31 - 1 tiles each
     if (chunk > (tile << 20)) chunk = tile << 20;
+    chunk = even_chunk(maxn, chunk, tile);
     const uint64_t nchunks = ceil_div(maxn, chunk);
     const uint64_t tpc = ceil_div(chunk, tile);
     const uint64_t per_launch = 0x7FFFFFFFull / ((uint64_t)b.nseg * tpc);  // chunks one launch can index: >= 63
@@ -509,7 +530,6 @@ struct Ctx {
     // The chunk only orders the tiles.  The one-source kernel on blocks of 1 GiB and more measured
     // 3 % faster on MI355X when it walks 64 MiB of a block before it moves to the next block.
     if (copy_mode && a.B * es >= kGatherBigBlock && chunk * es < kGatherBigChunk) chunk = kGatherBigChunk / es;
-    const uint64_t nchunks = ceil_div(a.B, chunk);
     Tuning t = tune;
     // the general-form kernel (operator other than the sum, or tree order) is
     // built for small workgroups and one vector per thread and rank
@@ -523,6 +543,8 @@ struct Ctx {
     }
     if (general && t.threads > kGenMaxThreads) t.threads = kGenMaxThreads;
     const uint64_t tile = tile_elems(dtype, t);
+    chunk = even_chunk(a.B, chunk, tile);
+    const uint64_t nchunks = ceil_div(a.B, chunk);
     const uint64_t tpc = ceil_div(chunk, tile);
     const uint64_t total = nchunks * (uint64_t)(one_block ? 1 : W) * tpc;
     if (total > 0x7FFFFFFFull) return fail(HCL_ERR_INVALID_ARG, "collective needs %llu tiles, more than one launch can index", (unsigned long long)total);
@@ -611,7 +633,7 @@ struct Inbox {
 // the outgoing slot of a step sit at addresses congruent modulo the block size; on some machines
 // (it depends on where the allocation lands physically) that cost the 2 GiB-block Reduce-Scatter
 // 4-7 % of bandwidth, and the 4 KiB took it away; where it cost nothing, the pad changed nothing.
-constexpr uint64_t kSlotPad = 4096;
+constexpr uint64_t kSlotPad = 4096;  // also leaves room for the partial to start up to 127 bytes into its slot
 uint64_t slot_bytes_for(uint64_t block_elems, uint64_t es) { return round_up(block_elems * es, 256) + kSlotPad; }
 
 hcl_status_t get_inbox(const Ctx& c, uint64_t block_elems, Inbox& ib) {
@@ -757,13 +779,16 @@ static hcl_status_t run_rs(Ctx& c, const BlockMap& bm, const void* const* own, c
           add_seg(a, in, local, fin[r], nullptr, n);
         }
       } else {
+        // inside its slot the partial starts at the block's own offset modulo 128 bytes, so that
+        // it is congruent with the local operands (the kernels align on 128-byte lines)
+        char* slot = ws ? ws + (uint64_t)b * ws_slot + ((uintptr_t)off(own[c.ring.order[0]], lo, es) & 127) : nullptr;
         const char* in;
         if (s == 0) in = off(first[p], lo, es);
-        else if (ws) in = ws + (uint64_t)b * ws_slot;
+        else if (ws) in = slot;
         else in = off(part[p], lo, es);
         char* out;
         if (last) out = fin[r];
-        else if (ws) out = ws + (uint64_t)b * ws_slot;
+        else if (ws) out = slot;
         else out = off(part[r], lo, es);
         if (last && push) {
           add_seg(a, in, local, out, push[r], n);
@@ -1073,8 +1098,10 @@ extern "C" hcl_status_t hcl_reduce_sim(const void* const* send, void* const* rec
     for (int k = 1; k <= W - 1; ++k) {
       const int r = c.ring.at(p0 + 1 + k), p = c.ring.at(p0 + k);
       // the travelling partial sum stays in the one workspace slot: read, combined, written back
-      const char* in = k == 1 ? (const char*)send[p] : ws;
-      char* out_p = k == W - 1 ? (char*)recv[root] : ws;
+      // (at the senders' offset modulo 128 bytes, so that it is congruent with them)
+      char* slot_p = ws + ((uintptr_t)send[c.ring.order[0]] & 127);
+      const char* in = k == 1 ? (const char*)send[p] : slot_p;
+      char* out_p = k == W - 1 ? (char*)recv[root] : slot_p;
       StepArgs a{};
       add_seg(a, in, send[r], out_p, nullptr, count);
       hcl_status_t s2 = c.launch(a, 2, 1, k < W - 1);

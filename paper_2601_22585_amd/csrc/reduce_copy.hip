@@ -35,10 +35,23 @@ __global__ void __launch_bounds__(1024) reduce_copy_vec(const StepArgs a) {
     // is what the last-level cache still holds, so it is read first
     const uint32_t t = a.reverse ? a.total_tiles - 1u - t0 : t0;
     const TilePos p = locate(t, a.tiles_per_chunk, a.nseg, a.chunk, tile, a.stagger);
-    const uint32_t len = tile_len(p, a.seg[p.d].n, a.chunk, tile);
+    // the segment's head, up to the first 128-byte boundary of its destination: element by
+    // element, by the tile that starts the segment; the tile grid covers what follows it
+    const uint32_t pre = head_elems<ES>(a.seg[p.d].dst0, a.seg[p.d].n);
+    if (p.lo == 0 && pre) {
+      const elem_t* h0 = reinterpret_cast<const elem_t*>(a.seg[p.d].src0);
+      const elem_t* h1 = reinterpret_cast<const elem_t*>(a.seg[p.d].src1);
+      for (uint32_t e = tid; e < pre; e += nthr) {
+        elem_t r = h0[e];
+        if (NSRC == 2) r = GEN ? op_elem<DT>(a.op, r, h1[e]) : Wire<DT>::hop_elem(r, h1[e]);
+        reinterpret_cast<elem_t*>(a.seg[p.d].dst0)[e] = r;
+        if (NDST == 2) reinterpret_cast<elem_t*>(a.seg[p.d].dst1)[e] = r;
+      }
+    }
+    const uint32_t len = tile_len(p, a.seg[p.d].n - pre, a.chunk, tile);
     if (len == 0) continue;
 
-    const uint64_t boff = p.lo * ES;
+    const uint64_t boff = (pre + p.lo) * ES;
     const char* s0 = a.seg[p.d].src0 + boff;
     const char* s1 = NSRC == 2 ? a.seg[p.d].src1 + boff : nullptr;
     char* d0 = a.seg[p.d].dst0 + boff;

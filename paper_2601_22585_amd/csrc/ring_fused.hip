@@ -38,62 +38,70 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
     uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
     if (blo > a.count) blo = a.count;
     if (bhi > a.count) bhi = a.count;
-    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
-    if (len == 0) continue;
+    // The block's head, up to the first 128-byte boundary, is done by the tile that starts the
+    // block (part 0: a few unaligned vectors and single elements); the tile grid covers the rest
+    // (part 1).  The boundary is that of the streams that carry most of the traffic: the W
+    // destinations of an All-Reduce, the W sources of a reduction to one owner.
+    const uint32_t pre = head_elems<ES>((to_all ? a.dst[0] : a.src[0]) + blo * ES, bhi - blo);
+    for (int part = (p.lo == 0 && pre) ? 0 : 1; part < 2; ++part) {
+      const uint64_t lo = part ? pre + p.lo : 0;  // first element inside the block
+      const uint32_t len = part ? tile_len(p, bhi - blo - pre, a.chunk, tile) : pre;
+      if (len == 0) continue;
 
-    const uint64_t voff = (blo + p.lo) * ES;  // offset inside a full vector
-    const uint32_t pc = a.pos[c];
-    const char* sp[W];
+      const uint64_t voff = (blo + lo) * ES;  // offset inside a full vector
+      const uint32_t pc = a.pos[c];
+      const char* sp[W];
 #pragma unroll
-    for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(pc + 1 + k) % W]] + voff;
+      for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(pc + 1 + k) % W]] + voff;
 
-    const uint32_t nvec = len / VE;
-    u32x4 v[U][W];
+      const uint32_t nvec = len / VE;
+      u32x4 v[U][W];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t vi = u * nthr + tid;
-      if (vi < nvec) {
+      for (int u = 0; u < U; ++u) {
+        const uint32_t vi = u * nthr + tid;
+        if (vi < nvec) {
 #pragma unroll
-        for (int k = 0; k < W; ++k) v[u][k] = ld16<NT>(sp[k] + vi * 16u);
+          for (int k = 0; k < W; ++k) v[u][k] = ld16<NT>(sp[k] + vi * 16u);
+        }
       }
-    }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t vi = u * nthr + tid;
-      if (vi < nvec) {
-        u32x4 acc;
+      for (int u = 0; u < U; ++u) {
+        const uint32_t vi = u * nthr + tid;
+        if (vi < nvec) {
+          u32x4 acc;
+          if (WIDE) {
+            acc = sum_wide<DT, W>(v[u]);
+          } else {
+            acc = v[u][0];
+#pragma unroll
+            for (int k = 1; k < W; ++k) acc = hop_vec<DT>(acc, v[u][k]);
+          }
+          if (to_all) {
+#pragma unroll
+            for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
+          } else {
+            st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + lo * ES + vi * 16u, acc);
+          }
+        }
+      }
+      const uint32_t e = nvec * VE + tid;
+      if (e < len) {
+        elem_t acc = reinterpret_cast<const elem_t*>(sp[0])[e];
         if (WIDE) {
-          acc = sum_wide<DT, W>(v[u]);
-        } else {
-          acc = v[u][0];
+          float f = widen1<DT>(acc);
 #pragma unroll
-          for (int k = 1; k < W; ++k) acc = hop_vec<DT>(acc, v[u][k]);
+          for (int k = 1; k < W; ++k) f = f + widen1<DT>(reinterpret_cast<const elem_t*>(sp[k])[e]);
+          acc = narrow1<DT>(f);
+        } else {
+#pragma unroll
+          for (int k = 1; k < W; ++k) acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(sp[k])[e]);
         }
         if (to_all) {
 #pragma unroll
-          for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
+          for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
         } else {
-          st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+          reinterpret_cast<elem_t*>(a.dst[c] + lo * ES)[e] = acc;
         }
-      }
-    }
-    const uint32_t e = nvec * VE + tid;
-    if (e < len) {
-      elem_t acc = reinterpret_cast<const elem_t*>(sp[0])[e];
-      if (WIDE) {
-        float f = widen1<DT>(acc);
-#pragma unroll
-        for (int k = 1; k < W; ++k) f = f + widen1<DT>(reinterpret_cast<const elem_t*>(sp[k])[e]);
-        acc = narrow1<DT>(f);
-      } else {
-#pragma unroll
-        for (int k = 1; k < W; ++k) acc = Wire<DT>::hop_elem(acc, reinterpret_cast<const elem_t*>(sp[k])[e]);
-      }
-      if (to_all) {
-#pragma unroll
-        for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
-      } else {
-        reinterpret_cast<elem_t*>(a.dst[c] + p.lo * ES)[e] = acc;
       }
     }
   }
@@ -110,40 +118,47 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
   for (uint32_t t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
     const TilePos p = locate(t, a.tiles_per_chunk, whole ? 1u : W, a.chunk, tile);
     const uint32_t c = whole ? a.root : p.d;
-    const uint32_t len = tile_len(p, a.B, a.chunk, tile);
-    if (len == 0) continue;
-    const char* s = a.src[c] + p.lo * ES;
-    const uint64_t voff = ((whole ? 0 : (uint64_t)c * a.B) + p.lo) * ES;
-    const uint32_t nvec = len / VE;
-    u32x4 v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t vi = u * nthr + tid;
-      if (vi < nvec) v[u] = ld16<NT>(s + vi * 16u);
-    }
-    for (uint32_t r = 0; r < W; ++r) {
-      char* d = a.dst[r] + voff;
+    // head of the block (up to the first 128-byte boundary of the W destination streams): part 0,
+    // by the tile that starts the block; the tile grid covers the rest: part 1
+    const uint64_t boff = whole ? 0 : (uint64_t)c * a.B;
+    const uint32_t pre = head_elems<ES>(a.dst[0] + boff * ES, a.B);
+    for (int part = (p.lo == 0 && pre) ? 0 : 1; part < 2; ++part) {
+      const uint64_t lo = part ? pre + p.lo : 0;
+      const uint32_t len = part ? tile_len(p, a.B - pre, a.chunk, tile) : pre;
+      if (len == 0) continue;
+      const char* s = a.src[c] + lo * ES;
+      const uint64_t voff = (boff + lo) * ES;
+      const uint32_t nvec = len / VE;
+      u32x4 v[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t vi = u * nthr + tid;
-        if (vi < nvec) st16<NT ? ST_STREAM : ST_PLAIN>(d + vi * 16u, v[u]);
+        if (vi < nvec) v[u] = ld16<NT>(s + vi * 16u);
       }
-    }
-    const uint32_t e = nvec * VE + tid;
-    if (e < len) {
-      // up to VE - 1 elements: the tail of a 16-byte vector (ES = 8 never gets here)
-      if (ES == 1) {
-        const uint8_t x = reinterpret_cast<const uint8_t*>(s)[e];
-        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint8_t*>(a.dst[r] + voff)[e] = x;
-      } else if (ES == 2) {
-        const uint16_t x = reinterpret_cast<const uint16_t*>(s)[e];
-        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint16_t*>(a.dst[r] + voff)[e] = x;
-      } else if (ES == 4) {
-        const uint32_t x = reinterpret_cast<const uint32_t*>(s)[e];
-        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint32_t*>(a.dst[r] + voff)[e] = x;
-      } else {
-        const uint64_t x = reinterpret_cast<const uint64_t*>(s)[e];
-        for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint64_t*>(a.dst[r] + voff)[e] = x;
+      for (uint32_t r = 0; r < W; ++r) {
+        char* d = a.dst[r] + voff;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t vi = u * nthr + tid;
+          if (vi < nvec) st16<NT ? ST_STREAM : ST_PLAIN>(d + vi * 16u, v[u]);
+        }
+      }
+      const uint32_t e = nvec * VE + tid;
+      if (e < len) {
+        // up to VE - 1 elements: the tail of a 16-byte vector (ES = 8 never gets here)
+        if (ES == 1) {
+          const uint8_t x = reinterpret_cast<const uint8_t*>(s)[e];
+          for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint8_t*>(a.dst[r] + voff)[e] = x;
+        } else if (ES == 2) {
+          const uint16_t x = reinterpret_cast<const uint16_t*>(s)[e];
+          for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint16_t*>(a.dst[r] + voff)[e] = x;
+        } else if (ES == 4) {
+          const uint32_t x = reinterpret_cast<const uint32_t*>(s)[e];
+          for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint32_t*>(a.dst[r] + voff)[e] = x;
+        } else {
+          const uint64_t x = reinterpret_cast<const uint64_t*>(s)[e];
+          for (uint32_t r = 0; r < W; ++r) reinterpret_cast<uint64_t*>(a.dst[r] + voff)[e] = x;
+        }
       }
     }
   }
@@ -289,52 +304,58 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
     uint64_t blo = whole ? 0 : (uint64_t)c * a.B, bhi = blo + a.B;
     if (blo > a.count) blo = a.count;
     if (bhi > a.count) bhi = a.count;
-    const uint32_t len = tile_len(p, bhi - blo, a.chunk, tile);
-    if (len == 0) continue;
+    // head of the block up to the first 128-byte boundary: part 0, by the tile that starts the
+    // block; the tile grid covers the rest: part 1 (as in the sum kernel)
+    const uint32_t pre = head_elems<ES>((to_all ? a.dst[0] : a.src[0]) + blo * ES, bhi - blo);
+    for (int part = (p.lo == 0 && pre) ? 0 : 1; part < 2; ++part) {
+      const uint64_t lo = part ? pre + p.lo : 0;
+      const uint32_t len = part ? tile_len(p, bhi - blo - pre, a.chunk, tile) : pre;
+      if (len == 0) continue;
 
-    const uint64_t voff = (blo + p.lo) * ES;
-    const uint32_t first = tree ? 0u : a.pos[c] + 1u;  // ring position of the first value to enter
-    const char* sp[W];
+      const uint64_t voff = (blo + lo) * ES;
+      const uint32_t first = tree ? 0u : a.pos[c] + 1u;  // ring position of the first value to enter
+      const char* sp[W];
 #pragma unroll
-    for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(first + k) % W]] + voff;
+      for (int k = 0; k < W; ++k) sp[k] = a.src[a.order[(first + k) % W]] + voff;
 
-    const uint32_t nvec = len / VE;
+      const uint32_t nvec = len / VE;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t vi = u * nthr + tid;
-      if (vi < nvec) {
-        u32x4 v[W];
+      for (int u = 0; u < U; ++u) {
+        const uint32_t vi = u * nthr + tid;
+        if (vi < nvec) {
+          u32x4 v[W];
 #pragma unroll
-        for (int k = 0; k < W; ++k) v[k] = ld16<NT>(sp[k] + vi * 16u);
-        const u32x4 acc = combine_vec<DT, W>(v, op, tree, wide);
-        if (to_all) {
+          for (int k = 0; k < W; ++k) v[k] = ld16<NT>(sp[k] + vi * 16u);
+          const u32x4 acc = combine_vec<DT, W>(v, op, tree, wide);
+          if (to_all) {
 #pragma unroll
-          for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
-        } else {
-          st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + p.lo * ES + vi * 16u, acc);
+            for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
+          } else {
+            st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + lo * ES + vi * 16u, acc);
+          }
         }
       }
-    }
-    const uint32_t e = nvec * VE + tid;
-    if (e < len) {
-      // one element: put it into the low bits of a word (or a 64-bit value) and combine those
-      elem_t acc;
-      if (sizeof(elem_t) == 8) {
-        uint64_t w1[W];
+      const uint32_t e = nvec * VE + tid;
+      if (e < len) {
+        // one element: put it into the low bits of a word (or a 64-bit value) and combine those
+        elem_t acc;
+        if (sizeof(elem_t) == 8) {
+          uint64_t w1[W];
 #pragma unroll
-        for (int k = 0; k < W; ++k) w1[k] = (uint64_t)reinterpret_cast<const elem_t*>(sp[k])[e];
-        acc = (elem_t)combine64<DT, W>(w1, op, tree);
-      } else {
-        uint32_t w1[W];
+          for (int k = 0; k < W; ++k) w1[k] = (uint64_t)reinterpret_cast<const elem_t*>(sp[k])[e];
+          acc = (elem_t)combine64<DT, W>(w1, op, tree);
+        } else {
+          uint32_t w1[W];
 #pragma unroll
-        for (int k = 0; k < W; ++k) w1[k] = (uint32_t)reinterpret_cast<const elem_t*>(sp[k])[e];
-        acc = (elem_t)combine_word<DT, W>(w1, op, tree, wide);
-      }
-      if (to_all) {
+          for (int k = 0; k < W; ++k) w1[k] = (uint32_t)reinterpret_cast<const elem_t*>(sp[k])[e];
+          acc = (elem_t)combine_word<DT, W>(w1, op, tree, wide);
+        }
+        if (to_all) {
 #pragma unroll
-        for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
-      } else {
-        reinterpret_cast<elem_t*>(a.dst[c] + p.lo * ES)[e] = acc;
+          for (int r = 0; r < W; ++r) reinterpret_cast<elem_t*>(a.dst[r] + voff)[e] = acc;
+        } else {
+          reinterpret_cast<elem_t*>(a.dst[c] + lo * ES)[e] = acc;
+        }
       }
     }
   }

@@ -376,6 +376,19 @@ __device__ __forceinline__ TilePos locate(uint32_t t, uint32_t tiles_per_chunk, 
   p.lo = p.j * chunk + (uint64_t)k * tile;
   return p;
 }
+// Head of a run of n elements of ES bytes that starts at `p`: the elements before the first
+// 128-byte boundary.  The tile that starts the run does them one by one and the tile grid covers
+// the rest, so that every 128-bit access of a wavefront is aligned and its 1 KiB covers whole cache
+// lines wherever the block map or the caller puts the run -- for every stream that is congruent
+// to `p` modulo 128 bytes, which equal block offsets in equally aligned buffers are.  (Blocks of
+// ceil(count / W) elements start at odd offsets for most counts; walking them unaligned cost
+// 14 % of bandwidth on MI355X.)
+template <uint32_t ES>
+__device__ __forceinline__ uint32_t head_elems(const void* p, uint64_t n) {
+  const uint32_t h = (uint32_t)((0u - (uint32_t)(uintptr_t)p) & 127u) / ES;
+  return n < h ? (uint32_t)n : h;
+}
+
 // Elements of this tile: up to the end of its chunk, clipped to the n elements
 // of the segment; 0 = nothing to do.
 __device__ __forceinline__ uint32_t tile_len(const TilePos& p, uint64_t n, uint64_t chunk, uint32_t tile) {

@@ -538,7 +538,7 @@ static void check_large(uint64_t n, int dtype, uint64_t chunk_bytes, int threads
   snprintf(d, sizeof d, "large reduce-scatter n=%llu dtype=%d chunk_bytes=%llu shape=%dx%d chains=%d", (unsigned long long)n, dtype,
            (unsigned long long)chunk_bytes, threads, unroll, two_chains ? 2 : 1);
   g_case = d;
-  const uintptr_t base = 0x200000000000ull, stride = 0x4000000000ull;  // 256 GiB apart
+  const uintptr_t base = 0x200000000000ull, stride = 0x80000000000ull;  // 8 TiB apart
   const void* send[16];
   void* recv[16];
   for (int r = 0; r < W; ++r) {
@@ -715,8 +715,8 @@ int main(int argc, char** argv) {
   // sizes beyond 32-bit byte offsets and beyond 2^31 - 1 tiles per step
   check_large((uint64_t)1 << 30, HCL_BF16, 4 << 20, 0, 0, false, 1);       // 2 GiB blocks, 16 GiB vectors
   check_large((uint64_t)1 << 30, HCL_BF16, 4 << 20, 0, 0, true, 2);
-  check_large((uint64_t)1 << 29, HCL_UINT8, 1, 64, 1, false, 3);            // one tile per byte: 2^32 tiles a step
-  check_large((uint64_t)1 << 29, HCL_UINT8, 1, 64, 1, true, 4);
+  check_large((uint64_t)1 << 39, HCL_UINT8, 1, 64, 1, false, 3);            // 512 GiB blocks in 1 KiB tiles: 2^32 tiles a step
+  check_large((uint64_t)1 << 39, HCL_UINT8, 1, 64, 1, true, 4);
   check_large(((uint64_t)1 << 30) + 12345, HCL_FP64, 0, 64, 1, false, 1);   // one chunk of 8 GiB per block
   check_large_slabs();
   if (g_fail) {
