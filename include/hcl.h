@@ -161,9 +161,11 @@ typedef struct hcl_opts {
                               (streaming) loads; a STEPWISE step whose output a later launch of
                               the call reads, and which fits the 256 MiB last-level cache, writes
                               it through the L2 so that the next launch finds it in that cache;
-                              all other stores are non-temporal.  1 = loads and stores
-                              non-temporal, 2 = loads non-temporal and step stores written
-                              through (FUSED: ordinary stores), -1 = ordinary loads and stores */
+                              the FUSED kernels write through while what they write fits that
+                              cache (the one-source kernel: unless it runs its shape for blocks
+                              of 1 GiB and more); all other stores are non-temporal.
+                              1 = loads and stores non-temporal, 2 = loads non-temporal and
+                              stores written through, -1 = ordinary loads and stores          */
   int fuse_rs_ag;          /* STEPWISE All-Reduce only: 1 = the last Reduce-Scatter step also
                               writes the finished block into the next rank's buffer and the
                               first All-Gather step is dropped (same bits, one read fewer)   */

@@ -542,6 +542,21 @@ struct Ctx {
       t.unroll = general ? kGenUnroll : fused_unroll(W);
     }
     if (general && t.threads > kGenMaxThreads) t.threads = kGenMaxThreads;
+    // Cache policy of the one-launch kernels, from sweeps on MI355X.  Loads are non-temporal.  The
+    // one-source kernel writes through the L2 (+1.5 to +5 % of HBM peak from 64 MiB to 4 GiB per
+    // rank) except in its four-vector shape for blocks of 1 GiB and more, where non-temporal
+    // stores are 9 points ahead.  The reductions write through while everything they write fits
+    // the last-level cache (All-Reduce over 8 ranks: +8 points at 16 MiB per rank, +13 at 32 MiB;
+    // over 16 ranks +11 at 16 MiB) and with non-temporal stores beyond (written through: -7 to +4
+    // at twice the cache, depending on where the buffers lie; -4 to +0.6 further up).
+    if (auto_nt) {
+      if (copy_mode) {
+        t.nt = t.unroll == 4 ? 2 : 1;
+      } else {
+        const uint64_t written = (a.mode == 0 ? (uint64_t)W : 1) * a.count * es;
+        t.nt = written <= kLastLevelCache ? 1 : 2;
+      }
+    }
     const uint64_t tile = tile_elems(dtype, t);
     chunk = even_chunk(a.B, chunk, tile);
     const uint64_t nchunks = ceil_div(a.B, chunk);

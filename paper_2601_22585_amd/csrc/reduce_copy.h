@@ -58,8 +58,7 @@ struct Tuning {
   int blocks;       // workgroups
   int unroll;       // 1, 2, 4, 8
   int nt;           // cache policy: 0 ordinary loads and stores; 1 non-temporal (streaming) loads, stores
-                    // written through the L2; 2 non-temporal loads and stores.  The fused kernels know
-                    // on (!= 0) and off
+                    // written through the L2; 2 non-temporal loads and stores
 };
 
 // Elements one tile covers for this dtype / tuning.

@@ -21,8 +21,12 @@ namespace hcl {
 // to the wire type after every addition -- the value the stepwise ring
 // produces, with each rank's element read once.
 // ---------------------------------------------------------------------------
-template <int DT, int W, bool NT, bool WIDE>
+// NT: 0 ordinary loads and stores; 1 non-temporal loads, stores written through the L2; 2
+// non-temporal loads and stores (as in the step kernels)
+template <int DT, int W, int NT, bool WIDE>
 __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
+  constexpr bool NTL = NT != 0;
+  constexpr int NTS = NT == 2 ? ST_STREAM : NT == 1 ? ST_THROUGH : ST_PLAIN;
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
   constexpr uint32_t VE = 16 / ES;
@@ -61,7 +65,7 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
         const uint32_t vi = u * nthr + tid;
         if (vi < nvec) {
 #pragma unroll
-          for (int k = 0; k < W; ++k) v[u][k] = ld16<NT>(sp[k] + vi * 16u);
+          for (int k = 0; k < W; ++k) v[u][k] = ld16<NTL>(sp[k] + vi * 16u);
         }
       }
 #pragma unroll
@@ -78,9 +82,9 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
           }
           if (to_all) {
 #pragma unroll
-            for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
+            for (int r = 0; r < W; ++r) st16<NTS>(a.dst[r] + voff + vi * 16u, acc);
           } else {
-            st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + lo * ES + vi * 16u, acc);
+            st16<NTS>(a.dst[c] + lo * ES + vi * 16u, acc);
           }
         }
       }
@@ -108,8 +112,10 @@ __global__ void __launch_bounds__(1024) ring_fused_vec(const FusedArgs a) {
 }
 
 // All-Gather in one launch: block c is read once from rank c and stored to all ranks.
-template <int ES, bool NT, int U>
+template <int ES, int NT, int U>
 __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
+  constexpr bool NTL = NT != 0;
+  constexpr int NTS = NT == 2 ? ST_STREAM : NT == 1 ? ST_THROUGH : ST_PLAIN;
   constexpr uint32_t VE = 16 / ES;
   const uint32_t tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t tile = nthr * VE * U;
@@ -133,14 +139,14 @@ __global__ void __launch_bounds__(1024) gather_fused_vec(const FusedArgs a) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t vi = u * nthr + tid;
-        if (vi < nvec) v[u] = ld16<NT>(s + vi * 16u);
+        if (vi < nvec) v[u] = ld16<NTL>(s + vi * 16u);
       }
       for (uint32_t r = 0; r < W; ++r) {
         char* d = a.dst[r] + voff;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const uint32_t vi = u * nthr + tid;
-          if (vi < nvec) st16<NT ? ST_STREAM : ST_PLAIN>(d + vi * 16u, v[u]);
+          if (vi < nvec) st16<NTS>(d + vi * 16u, v[u]);
         }
       }
       const uint32_t e = nvec * VE + tid;
@@ -285,8 +291,10 @@ __device__ __forceinline__ u32x4 combine_vec(const u32x4 (&v)[W], uint32_t op, b
   return acc;
 }
 
-template <int DT, int W, bool NT>
+template <int DT, int W, int NT>
 __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs a) {
+  constexpr bool NTL = NT != 0;
+  constexpr int NTS = NT == 2 ? ST_STREAM : NT == 1 ? ST_THROUGH : ST_PLAIN;
   typedef typename Wire<DT>::elem_t elem_t;
   constexpr uint32_t ES = sizeof(elem_t);
   constexpr uint32_t VE = 16 / ES;
@@ -325,13 +333,13 @@ __global__ void __launch_bounds__(kGenMaxThreads) ring_fused_gen(const FusedArgs
         if (vi < nvec) {
           u32x4 v[W];
 #pragma unroll
-          for (int k = 0; k < W; ++k) v[k] = ld16<NT>(sp[k] + vi * 16u);
+          for (int k = 0; k < W; ++k) v[k] = ld16<NTL>(sp[k] + vi * 16u);
           const u32x4 acc = combine_vec<DT, W>(v, op, tree, wide);
           if (to_all) {
 #pragma unroll
-            for (int r = 0; r < W; ++r) st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[r] + voff + vi * 16u, acc);
+            for (int r = 0; r < W; ++r) st16<NTS>(a.dst[r] + voff + vi * 16u, acc);
           } else {
-            st16<NT ? ST_STREAM : ST_PLAIN>(a.dst[c] + lo * ES + vi * 16u, acc);
+            st16<NTS>(a.dst[c] + lo * ES + vi * 16u, acc);
           }
         }
       }
@@ -375,8 +383,9 @@ int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
     constexpr int ES = sizeof(typename Wire<DT>::elem_t);
 #define HCL_CASE(UU)                                                            \
   case UU:                                                                      \
-    if (t.nt) gather_fused_vec<ES, true, UU><<<g, b, 0, s>>>(a);       \
-    else gather_fused_vec<ES, false, UU><<<g, b, 0, s>>>(a);                    \
+    if (t.nt == 2) gather_fused_vec<ES, 2, UU><<<g, b, 0, s>>>(a);              \
+    else if (t.nt == 1) gather_fused_vec<ES, 1, UU><<<g, b, 0, s>>>(a);         \
+    else gather_fused_vec<ES, 0, UU><<<g, b, 0, s>>>(a);                        \
     break;
     switch (t.unroll) {
       HCL_CASE(1) HCL_CASE(2) HCL_CASE(4)
@@ -390,11 +399,13 @@ int launch_fused_sum(const FusedArgs& a, const Tuning& t, void* stream) {
 #define HCL_CASE(WW)                                                                      \
   case WW:                                                                                \
     if (wide) {                                                                           \
-      if (t.nt) ring_fused_vec<DT, WW, true, kW><<<g, b, 0, s>>>(a);             \
-      else ring_fused_vec<DT, WW, false, kW><<<g, b, 0, s>>>(a);                          \
+      if (t.nt == 2) ring_fused_vec<DT, WW, 2, kW><<<g, b, 0, s>>>(a);                    \
+      else if (t.nt == 1) ring_fused_vec<DT, WW, 1, kW><<<g, b, 0, s>>>(a);               \
+      else ring_fused_vec<DT, WW, 0, kW><<<g, b, 0, s>>>(a);                              \
     } else {                                                                              \
-      if (t.nt) ring_fused_vec<DT, WW, true, false><<<g, b, 0, s>>>(a);          \
-      else ring_fused_vec<DT, WW, false, false><<<g, b, 0, s>>>(a);                       \
+      if (t.nt == 2) ring_fused_vec<DT, WW, 2, false><<<g, b, 0, s>>>(a);                 \
+      else if (t.nt == 1) ring_fused_vec<DT, WW, 1, false><<<g, b, 0, s>>>(a);            \
+      else ring_fused_vec<DT, WW, 0, false><<<g, b, 0, s>>>(a);                           \
     }                                                                                     \
     break;
   switch (a.W) {
@@ -414,8 +425,9 @@ int launch_fused_gen(const FusedArgs& a, const Tuning& t, void* stream) {
   if (t.threads > kGenMaxThreads) return (int)hipErrorInvalidValue;
 #define HCL_CASE(WW)                                                              \
   case WW:                                                                        \
-    if (t.nt) ring_fused_gen<DT, WW, true><<<g, b, 0, s>>>(a);           \
-    else ring_fused_gen<DT, WW, false><<<g, b, 0, s>>>(a);                        \
+    if (t.nt == 2) ring_fused_gen<DT, WW, 2><<<g, b, 0, s>>>(a);                  \
+    else if (t.nt == 1) ring_fused_gen<DT, WW, 1><<<g, b, 0, s>>>(a);             \
+    else ring_fused_gen<DT, WW, 0><<<g, b, 0, s>>>(a);                            \
     break;
   switch (a.W) {
     HCL_CASE(2) HCL_CASE(3) HCL_CASE(4) HCL_CASE(5) HCL_CASE(6) HCL_CASE(7) HCL_CASE(8) HCL_CASE(9)
