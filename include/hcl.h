@@ -68,7 +68,7 @@ extern "C" {
 #endif
 
 #define HCL_MAX_RANKS 16
-#define HCL_VERSION 103
+#define HCL_VERSION 104
 /* size of the library-owned scratch array behind hcl_reduce_scatter_sim_static */
 #define HCL_STATIC_SCRATCH_BYTES (32u << 20)
 

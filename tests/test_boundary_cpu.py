@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     L = hcl.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert hcl.version() == 103
+    assert hcl.version() == 104
 
 
 def _call_ar(send, recv, W, count, dtype=hcl.FP32, op=hcl.SUM, chunk=0, **opt):
